@@ -1,0 +1,191 @@
+/* specexit.h - C ABI of the SpecExit decode-round hot path for AMD MI355X (gfx950).
+ *
+ * One decode round of SpecExit (arXiv 2509.24248, Algorithm 1) is, per sequence:
+ *   k x  specexit_draft_step      draft ("MTP") forward with the widened head (Sec. 3.1, Eq. 1)
+ *   1 x  specexit_verify_attn     target attention over [last accepted | draft candidates]
+ *                                 with tree attention (Alg. 1), once per target layer
+ *   1 x  specexit_lmhead_argmax   target logits -> recover / verification tokens (Alg. 1)
+ *   1 x  specexit_accept_exit     acceptance, signal smoothing, stop thresholds and the
+ *                                 step-split exit (Alg. 1; Sec. 3.3; Appendix)
+ *
+ * Conventions
+ *   - Every array argument is a DEVICE pointer owned by the caller unless marked [host].
+ *     Descriptor structs are host structs read at call time; their first field is
+ *     struct_size = sizeof(the struct) as compiled by the caller.
+ *   - Calls only enqueue kernels on `stream` (a hipStream_t passed as void*; NULL = the
+ *     default stream).  They never allocate or free device memory, never synchronise and
+ *     never copy to the host, so a round may be captured in a HIP graph by the caller.
+ *   - Scratch memory is the caller's `workspace` (256-byte aligned), at least as large as
+ *     the matching *_workspace_bytes() query says.  Its contents are undefined afterwards.
+ *   - Return value: SPECEXIT_OK or a negative error code; specexit_last_error() then
+ *     returns a thread-local description.  No kernel is launched when validation fails.
+ *   - Contents of device arrays (token ids, page indices, lengths) are trusted: ids and
+ *     page numbers out of range are undefined behaviour.
+ *   - dtype selects the storage type of weights, KV caches, q, hidden states and the
+ *     attention output (SPECEXIT_F32 or SPECEXIT_BF16).  Accumulation, softmax, norms and
+ *     activations are always fp32.  All matrices are row-major [out, in].
+ */
+#ifndef SPECEXIT_H
+#define SPECEXIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPECEXIT_OK            0
+#define SPECEXIT_EINVAL       (-1)  /* null pointer, bad size, inconsistent shapes            */
+#define SPECEXIT_EUNSUPPORTED (-2)  /* shape or type outside what the kernels implement       */
+#define SPECEXIT_EWORKSPACE   (-3)  /* workspace missing, misaligned or too small             */
+#define SPECEXIT_ELAUNCH      (-4)  /* the HIP runtime refused a launch                       */
+
+typedef enum { SPECEXIT_F32 = 0, SPECEXIT_BF16 = 1 } specexit_dtype;
+typedef enum { SPECEXIT_KV_CONTIG = 0, SPECEXIT_KV_PAGED = 1 } specexit_kv_layout;
+
+/* Limits: 1 <= n_q <= 64 (one mask bit per block entry); head_dim in {64, 128};
+ * n_q_heads % n_kv_heads == 0; (n_q_heads / n_kv_heads) * n_q <= 128;
+ * page_size a multiple of 16; hidden, intermediate, n_q_heads*head_dim multiples of 64. */
+#define SPECEXIT_MAX_NQ 64
+#define SPECEXIT_N_SIGNALS 3
+
+/* Draft model dimensions (the draft layer mirrors the target's attention geometry). */
+typedef struct {
+  uint32_t struct_size;
+  int32_t dtype;           /* specexit_dtype */
+  int32_t hidden;          /* D */
+  int32_t n_q_heads, n_kv_heads, head_dim;
+  int32_t intermediate;    /* I, width of the gated MLP */
+  int32_t vocab;           /* V; the head has V + 3 rows */
+  float rms_eps;           /* RMSNorm epsilon */
+  float rope_theta;        /* rotary base */
+  int32_t rem_activation;  /* remaining-length head: 0 = max(0, expm1(z)) (inverse of the
+                              log(1+r) training target, Eq. 5), 1 = sigmoid, 2 = identity */
+} specexit_model_desc;
+
+/* Draft weights, dtype = desc.dtype, row-major [out, in].  The three norm vectors are
+ * also stored in dtype.  w_head rows: 0..V-1 = W_tok, V = W_conf, V+1 = W_prog,
+ * V+2 = W_rem (Eq. 1). */
+typedef struct {
+  uint32_t struct_size;
+  const void *embed;     /* [V, D]            */
+  const void *w_fc;      /* [D, 2D]  applied to [embedding ; hidden_in] */
+  const void *ln_attn, *ln_mlp, *ln_final; /* [D] */
+  const void *w_q;       /* [Hq*d, D]         */
+  const void *w_k, *w_v; /* [Hkv*d, D]        */
+  const void *w_o;       /* [D, Hq*d]         */
+  const void *w_gate, *w_up; /* [I, D]        */
+  const void *w_down;    /* [D, I]            */
+  const void *w_head;    /* [V+3, D]          */
+} specexit_draft_weights;
+
+/* One layer's K/V cache.
+ *   CONTIG: k, v are [B, n_kv_heads, l_max, head_dim].
+ *   PAGED : k, v are [n_pages, n_kv_heads, page_size, head_dim]; page_table is
+ *           [B, max_pages_per_seq] int32; token t of sequence b lives in page
+ *           page_table[b, t / page_size], slot t % page_size.  l_max is then
+ *           max_pages_per_seq * page_size.
+ * Table entries past a sequence's last used page are never read. */
+typedef struct {
+  uint32_t struct_size;
+  int32_t layout;        /* specexit_kv_layout */
+  int32_t dtype;
+  int32_t n_kv_heads, head_dim;
+  void *k, *v;
+  const int32_t *page_table;
+  int32_t page_size, max_pages_per_seq;
+  int64_t l_max, n_pages;
+} specexit_kv_view;
+
+/* Exit controller settings.  Defaults of the paper: alpha 0.1 (Appendix, EWMA);
+ * confidence > 0.8, progress > 0.3, remaining < 200 for the combined rule, or
+ * 0.9 / 0.8 / 100 with a single bit of signal_mask (Appendix, "Stop Threshold"). */
+typedef struct {
+  uint32_t struct_size;
+  float alpha, thr_conf, thr_prog, thr_rem;
+  uint32_t signal_mask;    /* bit 0 confidence, 1 progress, 2 remaining; ANDed */
+  int32_t smoother;        /* 0 EWMA, 1 none (raw signal) */
+  int32_t split_pick;      /* 0 earliest step-split token in the accepted path, 1 latest */
+  int32_t check_root;      /* 1: the block root may also act as the step-split token */
+  int32_t stop_think_token;
+} specexit_exit_cfg;
+
+/* ---- stage 1: draft step (Sec. 3.1 Eq. 1; Sec. 3.2 Eqs. 3-5; Alg. 1, first loop line) ----
+ * For each of the B rows: x = W_fc [embed[tok] ; hidden_in]; one pre-norm decoder layer
+ * (RMSNorm, GQA attention with rotary embedding over the draft's own cache positions
+ * 0..pos including the entry written now at pos, residual, RMSNorm, gated SiLU MLP,
+ * residual) -> hidden_out; z = W_head RMSNorm(hidden_out); next_tok = argmax z[0:V]
+ * (lowest index on ties); sig_raw = z[V:V+3]; sig = (sigmoid, sigmoid, rem_activation).
+ * draft_kv is updated in place at position pos[b].  hidden_in/hidden_out are [B, D] in
+ * dtype and may not alias.  1 <= B <= 64. */
+int32_t specexit_draft_step(const specexit_model_desc *desc, const specexit_draft_weights *w,
+                            const specexit_kv_view *draft_kv, int32_t B,
+                            const int32_t *tok /*[B]*/, const void *hidden_in /*[B,D]*/,
+                            const int32_t *pos /*[B]*/,
+                            void *hidden_out /*[B,D]*/, int32_t *next_tok /*[B]*/,
+                            float *sig_raw /*[B,3]*/, float *sig /*[B,3]*/,
+                            void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
+size_t specexit_draft_step_workspace_bytes(const specexit_model_desc *desc,
+                                           const specexit_kv_view *draft_kv, int32_t B);
+
+/* ---- stage 2: verification attention (Alg. 1, "forward through M_t with tree attention") ----
+ * out[b,i,h,:] = sum_j softmax_j(scale * q[b,i,h,:] . K[j]) V[j] over the visible cache
+ * positions j of query i: the context 0..ctx_len[b]-1 plus the block entries
+ * ctx_len[b]+t whose bit t is set in mask[b,i] (mask NULL = chain: bits 0..i).  The
+ * block's K/V must already be stored at positions ctx_len[b] .. ctx_len[b]+n_q-1.
+ * Query head h reads KV head h / (n_q_heads / n_kv_heads).  q and out are
+ * [B, n_q, n_q_heads, head_dim] in kv->dtype.  Every mask row must have at least one
+ * visible position (bit i of row i is normally set). */
+int32_t specexit_verify_attn(const specexit_kv_view *kv, int32_t B, int32_t n_q, int32_t n_q_heads,
+                             const void *q, const int32_t *ctx_len /*[B]*/,
+                             const uint64_t *mask /*[B,n_q] or NULL*/, float scale, void *out,
+                             void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
+size_t specexit_verify_attn_workspace_bytes(const specexit_kv_view *kv, int32_t B, int32_t n_q,
+                                            int32_t n_q_heads);
+
+/* ---- stage 3: LM head -> argmax (Alg. 1, "target model recover token"; greedy) ----
+ * z = hidden . w^T with w [V + n_extra, D]; argmax[r] = lowest index of the maximum of
+ * z[r, 0:V].  Rows V.. of w (the widened head's signal rows, Eq. 1) never enter the
+ * argmax; their products go to extra_out [M, n_extra].  max_logit, extra_out and
+ * logits_dbg ([M, V] fp32, every logit; for tests) may be NULL.  1 <= M <= 144. */
+int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra,
+                               const void *hidden /*[M,D]*/, const void *w /*[V+n_extra,D]*/,
+                               int32_t *argmax /*[M]*/, float *max_logit /*[M]*/,
+                               float *extra_out /*[M,n_extra]*/, float *logits_dbg /*[M,V]*/,
+                               void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
+size_t specexit_lmhead_argmax_workspace_bytes(int32_t dtype, int32_t M, int32_t D, int32_t V,
+                                              int32_t n_extra);
+
+/* ---- stages 4 + 5: acceptance, smoothing, exit rule (Alg. 1; Sec. 3.3; Appendix) ----
+ * Per sequence b:
+ *  smoothing  if is_thinking: x = sig on the first observation (n_obs == 0) or when
+ *             smoother == 1, else x = alpha*sig + (1-alpha)*x; n_obs += 1.
+ *  accept     walk from node 0: move to the lowest-index child c of the current node with
+ *             block_tok[c] == target_argmax[current]; accept_path lists the nodes entered
+ *             (-1 padded), accept_len their number, last_node the final node,
+ *             recover_tok = target_argmax[last_node].  parent NULL = chain (parent i-1).
+ *  exit       pass = AND over signal_mask of (x0 > thr_conf, x1 > thr_prog, x2 < thr_rem).
+ *             If is_thinking and pass and an accepted draft token is in split_tok: the
+ *             path is cut right after that token (earliest or latest per split_pick),
+ *             recover_tok = stop_think_token, is_thinking = 0, exit_flag = 1.
+ *  new_ctx_len = ctx_len + 1 + accept_len.
+ * ewma [B,3], n_obs [B], is_thinking [B] are in/out state.  split_tok is sorted
+ * ascending, S >= 0.  block_tok/parent/target_argmax are [B, n_q]. */
+int32_t specexit_accept_exit(const specexit_exit_cfg *cfg, int32_t B, int32_t n_q,
+                             const int32_t *block_tok, const int32_t *parent,
+                             const int32_t *target_argmax, const float *sig /*[B,3]*/,
+                             const int32_t *ctx_len /*[B]*/, const int32_t *split_tok, int32_t S,
+                             float *ewma, int32_t *n_obs, int32_t *is_thinking,
+                             int32_t *accept_len /*[B]*/, int32_t *accept_path /*[B,n_q]*/,
+                             int32_t *recover_tok /*[B]*/, int32_t *last_node /*[B]*/,
+                             int32_t *exit_flag /*[B]*/, int32_t *new_ctx_len /*[B]*/,
+                             uint32_t flags, void *stream);
+
+const char *specexit_last_error(void); /* [host] thread-local, never NULL */
+uint32_t specexit_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPECEXIT_H */

@@ -228,6 +228,7 @@ def draft_step(dims: DraftDims, w: dict, k_cache, v_cache, tok, hidden_in, pos,
     sig_raw = np.empty((B, 3), dtype=F64)
     next_tok = np.empty(B, dtype=np.int64)
     attn_out = np.empty((B, Hq * d), dtype=F64)
+    h_final = np.empty((B, D), dtype=F64)
     for b in range(B):
         e = np.asarray(w["embed"][int(tok[b])], dtype=F64)
         g = np.asarray(hidden_in[b], dtype=F64)
@@ -260,12 +261,14 @@ def draft_step(dims: DraftDims, w: dict, k_cache, v_cache, tok, hidden_in, pos,
         y = a + linear(act[None, :], w["w_down"])[0]
         hidden_out[b] = y
         h_fin = rmsnorm(y, w["ln_final"], dims.rms_eps)
+        h_final[b] = h_fin
         z = linear(h_fin[None, :], w["w_head"])[0]
         logits[b] = z[:V]
         sig_raw[b] = z[V:V + 3]
         next_tok[b] = argmax_lowest(z[:V])
     return {"hidden_out": hidden_out, "next_tok": next_tok, "sig_raw": sig_raw,
-            "sig": signal_activations(sig_raw), "logits": logits, "attn_out": attn_out}
+            "sig": signal_activations(sig_raw), "logits": logits, "attn_out": attn_out,
+            "h_final": h_final}
 
 
 # ---------------------------------------------------------------------------

@@ -1,0 +1,223 @@
+"""ctypes binding of libspecexit.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls, takes torch
+tensors that already live on the GPU (PyTorch is used for device memory and
+streams, nothing else) and passes their addresses through.  There is no CPU
+fallback: if the library is missing, importing this module raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libspecexit.so")
+
+F32, BF16 = 0, 1
+KV_CONTIG, KV_PAGED = 0, 1
+OK, EINVAL, EUNSUPPORTED, EWORKSPACE, ELAUNCH = 0, -1, -2, -3, -4
+
+EXPORTS = [
+    "specexit_draft_step", "specexit_draft_step_workspace_bytes",
+    "specexit_verify_attn", "specexit_verify_attn_workspace_bytes",
+    "specexit_lmhead_argmax", "specexit_lmhead_argmax_workspace_bytes",
+    "specexit_accept_exit", "specexit_last_error", "specexit_version",
+]
+
+
+class SpecExitError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"specexit error {code}: {msg}")
+        self.code = code
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("dtype", C.c_int32), ("hidden", C.c_int32),
+                ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("intermediate", C.c_int32), ("vocab", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_theta", C.c_float), ("rem_activation", C.c_int32)]
+
+
+WEIGHT_NAMES = ["embed", "w_fc", "ln_attn", "ln_mlp", "ln_final", "w_q", "w_k", "w_v", "w_o",
+                "w_gate", "w_up", "w_down", "w_head"]
+
+
+class DraftWeights(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32)] + [(n, C.c_void_p) for n in WEIGHT_NAMES]
+
+
+class KVView(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("layout", C.c_int32), ("dtype", C.c_int32),
+                ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("k", C.c_void_p), ("v", C.c_void_p),
+                ("page_table", C.c_void_p), ("page_size", C.c_int32), ("max_pages_per_seq", C.c_int32),
+                ("l_max", C.c_int64), ("n_pages", C.c_int64)]
+
+
+class ExitCfg(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("alpha", C.c_float), ("thr_conf", C.c_float),
+                ("thr_prog", C.c_float), ("thr_rem", C.c_float), ("signal_mask", C.c_uint32),
+                ("smoother", C.c_int32), ("split_pick", C.c_int32), ("check_root", C.c_int32),
+                ("stop_think_token", C.c_int32)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2509_24248_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, u32, sz, f32 = C.c_void_p, C.c_int32, C.c_uint32, C.c_size_t, C.c_float
+    lib.specexit_last_error.restype = C.c_char_p
+    lib.specexit_version.restype = u32
+    lib.specexit_draft_step_workspace_bytes.restype = sz
+    lib.specexit_draft_step_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(KVView), i32]
+    lib.specexit_draft_step.restype = i32
+    lib.specexit_draft_step.argtypes = [C.POINTER(ModelDesc), C.POINTER(DraftWeights), C.POINTER(KVView), i32,
+                                        vp, vp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
+    lib.specexit_verify_attn_workspace_bytes.restype = sz
+    lib.specexit_verify_attn_workspace_bytes.argtypes = [C.POINTER(KVView), i32, i32, i32]
+    lib.specexit_verify_attn.restype = i32
+    lib.specexit_verify_attn.argtypes = [C.POINTER(KVView), i32, i32, i32, vp, vp, vp, f32, vp, vp, sz, u32, vp]
+    lib.specexit_lmhead_argmax_workspace_bytes.restype = sz
+    lib.specexit_lmhead_argmax_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+    lib.specexit_lmhead_argmax.restype = i32
+    lib.specexit_lmhead_argmax.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
+    lib.specexit_accept_exit.restype = i32
+    lib.specexit_accept_exit.argtypes = [C.POINTER(ExitCfg), i32, i32, vp, vp, vp, vp, vp, vp, i32,
+                                         vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+    return lib
+
+
+LIB = _load()
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        raise SpecExitError(rc, LIB.specexit_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def dtype_code(t: torch.dtype) -> int:
+    if t == torch.float32:
+        return F32
+    if t == torch.bfloat16:
+        return BF16
+    raise ValueError(f"unsupported storage type {t}")
+
+
+def last_error() -> str:
+    return LIB.specexit_last_error().decode()
+
+
+def version() -> int:
+    return int(LIB.specexit_version())
+
+
+def model_desc(dtype: int, hidden: int, n_q_heads: int, n_kv_heads: int, head_dim: int, intermediate: int,
+               vocab: int, rms_eps: float = 1e-6, rope_theta: float = 1e6, rem_activation: int = 0) -> ModelDesc:
+    return ModelDesc(C.sizeof(ModelDesc), dtype, hidden, n_q_heads, n_kv_heads, head_dim, intermediate, vocab,
+                     rms_eps, rope_theta, rem_activation)
+
+
+def draft_weights(tensors: dict) -> DraftWeights:
+    """tensors: name -> device tensor for every name in WEIGHT_NAMES (kept alive by the caller)."""
+    w = DraftWeights()
+    w.struct_size = C.sizeof(DraftWeights)
+    for n in WEIGHT_NAMES:
+        t = tensors[n]
+        assert t.is_cuda and t.is_contiguous()
+        setattr(w, n, t.data_ptr())
+    return w
+
+
+def kv_view(k: torch.Tensor, v: torch.Tensor, page_table: Optional[torch.Tensor] = None) -> KVView:
+    """contiguous: k, v [B, Hkv, l_max, d]; paged: k, v [n_pages, Hkv, page_size, d] plus
+    page_table [B, max_pages] int32."""
+    assert k.is_cuda and k.is_contiguous() and v.is_contiguous() and k.shape == v.shape
+    kv = KVView()
+    kv.struct_size = C.sizeof(KVView)
+    kv.dtype = dtype_code(k.dtype)
+    kv.n_kv_heads = k.shape[1]
+    kv.head_dim = k.shape[3]
+    kv.k, kv.v = k.data_ptr(), v.data_ptr()
+    if page_table is None:
+        kv.layout = KV_CONTIG
+        kv.page_table = None
+        kv.page_size, kv.max_pages_per_seq = 16, 0
+        kv.l_max, kv.n_pages = k.shape[2], 0
+    else:
+        assert page_table.dtype == torch.int32 and page_table.is_cuda and page_table.is_contiguous()
+        kv.layout = KV_PAGED
+        kv.page_table = page_table.data_ptr()
+        kv.page_size, kv.max_pages_per_seq = k.shape[2], page_table.shape[1]
+        kv.l_max, kv.n_pages = page_table.shape[1] * k.shape[2], k.shape[0]
+    return kv
+
+
+def exit_cfg(alpha=0.1, thr_conf=0.8, thr_prog=0.3, thr_rem=200.0, signal_mask=0b111, smoother=0, split_pick=0,
+             check_root=0, stop_think_token=0) -> ExitCfg:
+    return ExitCfg(C.sizeof(ExitCfg), alpha, thr_conf, thr_prog, thr_rem, signal_mask, smoother, split_pick,
+                   check_root, stop_think_token)
+
+
+def _ws_args(ws: Optional[torch.Tensor]):
+    if ws is None:
+        return None, 0
+    return C.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def specexit_draft_step_workspace_bytes(desc: ModelDesc, draft_kv: KVView, B: int) -> int:
+    return int(LIB.specexit_draft_step_workspace_bytes(C.byref(desc), C.byref(draft_kv), B))
+
+
+def specexit_draft_step(desc: ModelDesc, w: DraftWeights, draft_kv: KVView, B: int, tok, hidden_in, pos,
+                        hidden_out, next_tok, sig_raw, sig, workspace, flags: int = 0, stream=None) -> None:
+    wp, wb = _ws_args(workspace)
+    _check(LIB.specexit_draft_step(C.byref(desc), C.byref(w), C.byref(draft_kv), B, _ptr(tok), _ptr(hidden_in),
+                                   _ptr(pos), _ptr(hidden_out), _ptr(next_tok), _ptr(sig_raw), _ptr(sig),
+                                   wp, wb, flags, _stream(stream)))
+
+
+def specexit_verify_attn_workspace_bytes(kv: KVView, B: int, n_q: int, n_q_heads: int) -> int:
+    return int(LIB.specexit_verify_attn_workspace_bytes(C.byref(kv), B, n_q, n_q_heads))
+
+
+def specexit_verify_attn(kv: KVView, B: int, n_q: int, n_q_heads: int, q, ctx_len, mask, scale: float, out,
+                         workspace, flags: int = 0, stream=None) -> None:
+    wp, wb = _ws_args(workspace)
+    _check(LIB.specexit_verify_attn(C.byref(kv), B, n_q, n_q_heads, _ptr(q), _ptr(ctx_len), _ptr(mask),
+                                    C.c_float(scale), _ptr(out), wp, wb, flags, _stream(stream)))
+
+
+def specexit_lmhead_argmax_workspace_bytes(dtype: int, M: int, D: int, V: int, n_extra: int = 0) -> int:
+    return int(LIB.specexit_lmhead_argmax_workspace_bytes(dtype, M, D, V, n_extra))
+
+
+def specexit_lmhead_argmax(dtype: int, M: int, D: int, V: int, n_extra: int, hidden, w, argmax, max_logit=None,
+                           extra_out=None, logits_dbg=None, workspace=None, flags: int = 0, stream=None) -> None:
+    wp, wb = _ws_args(workspace)
+    _check(LIB.specexit_lmhead_argmax(dtype, M, D, V, n_extra, _ptr(hidden), _ptr(w), _ptr(argmax),
+                                      _ptr(max_logit), _ptr(extra_out), _ptr(logits_dbg), wp, wb, flags,
+                                      _stream(stream)))
+
+
+def specexit_accept_exit(cfg: ExitCfg, B: int, n_q: int, block_tok, parent, target_argmax, sig, ctx_len,
+                         split_tok, S: int, ewma, n_obs, is_thinking, accept_len, accept_path, recover_tok,
+                         last_node, exit_flag, new_ctx_len, flags: int = 0, stream=None) -> None:
+    _check(LIB.specexit_accept_exit(C.byref(cfg), B, n_q, _ptr(block_tok), _ptr(parent), _ptr(target_argmax),
+                                    _ptr(sig), _ptr(ctx_len), _ptr(split_tok), S, _ptr(ewma), _ptr(n_obs),
+                                    _ptr(is_thinking), _ptr(accept_len), _ptr(accept_path), _ptr(recover_tok),
+                                    _ptr(last_node), _ptr(exit_flag), _ptr(new_ctx_len), flags, _stream(stream)))

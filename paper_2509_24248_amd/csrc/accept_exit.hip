@@ -1,0 +1,104 @@
+// Stages 4 and 5 of the round (Alg. 1): greedy acceptance of the draft block against the
+// target's argmax tokens, smoothing of the three exit signals (Appendix, EWMA with
+// alpha = 0.1), the stop thresholds (Appendix, "Stop Threshold") and the step-split gate
+// with truncation (Sec. 3.3 "Stopping Conditions").  One thread per sequence: the work is
+// a few dozen integer operations, so the kernel costs one launch and nothing else, which
+// is the point the paper makes against probing-based exits.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sx {
+
+namespace {
+
+__device__ __forceinline__ bool in_sorted(const int32_t* a, int n, int32_t key) {
+  int lo = 0, hi = n;
+  while (lo < hi) {
+    const int mid = (lo + hi) >> 1;
+    const int32_t v = a[mid];
+    if (v == key) return true;
+    if (v < key) lo = mid + 1; else hi = mid;
+  }
+  return false;
+}
+
+__global__ __launch_bounds__(64) void k_accept_exit(const ExitArgs a) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= a.B) return;
+  const int n = a.n_q;
+  const int32_t* tok = a.block_tok + static_cast<size_t>(b) * n;
+  const int32_t* am = a.target_argmax + static_cast<size_t>(b) * n;
+  const int32_t* par = a.parent ? a.parent + static_cast<size_t>(b) * n : nullptr;
+  int32_t* path = a.accept_path + static_cast<size_t>(b) * n;
+
+  // ---- smoothing: x_t = alpha s_t + (1 - alpha) x_{t-1}; the first observation seeds x
+  int thinking = a.is_thinking[b];
+  float x[3];
+#pragma unroll
+  for (int j = 0; j < 3; ++j) x[j] = a.ewma[b * 3 + j];
+  if (thinking) {
+    const int seen = a.n_obs[b];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+      const float s = a.sig[b * 3 + j];
+      x[j] = (a.smoother == 1 || seen == 0) ? s : __fadd_rn(__fmul_rn(a.alpha, s), __fmul_rn(1.0f - a.alpha, x[j]));
+      a.ewma[b * 3 + j] = x[j];
+    }
+    a.n_obs[b] = seen + 1;
+  }
+
+  // ---- acceptance: follow matching children from the root
+  int cur = 0, len = 0;
+  while (true) {
+    int nxt = -1;
+    const int32_t want = am[cur];
+    for (int c = cur + 1; c < n; ++c) {
+      const int p = par ? par[c] : c - 1;
+      if (p == cur && tok[c] == want) { nxt = c; break; }
+    }
+    if (nxt < 0) break;
+    path[len++] = nxt;
+    cur = nxt;
+  }
+  int32_t t_rec = am[cur];
+
+  // ---- exit gate
+  bool pass = true;
+  if (a.signal_mask & 1u) pass = pass && (x[0] > a.thr_conf);
+  if (a.signal_mask & 2u) pass = pass && (x[1] > a.thr_prog);
+  if (a.signal_mask & 4u) pass = pass && (x[2] < a.thr_rem);
+  int flag = 0;
+  if (thinking && pass) {
+    int cut = -1;  // number of accepted drafts kept when the exit fires
+    if (a.check_root && in_sorted(a.split_tok, a.S, tok[0])) cut = 0;
+    for (int j = 0; j < len; ++j) {
+      if (in_sorted(a.split_tok, a.S, tok[path[j]])) {
+        if (a.split_pick == 0) { if (cut < 0) cut = j + 1; }
+        else cut = j + 1;
+      }
+    }
+    if (cut >= 0) {
+      len = cut;
+      cur = len ? path[len - 1] : 0;
+      t_rec = a.stop_think_token;
+      thinking = 0;
+      flag = 1;
+      a.is_thinking[b] = 0;
+    }
+  }
+  for (int j = len; j < n; ++j) path[j] = -1;
+  a.accept_len[b] = len;
+  a.recover_tok[b] = t_rec;
+  a.last_node[b] = cur;
+  a.exit_flag[b] = flag;
+  a.new_ctx_len[b] = a.ctx_len[b] + 1 + len;
+}
+
+}  // namespace
+
+hipError_t launch_accept_exit(const ExitArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(k_accept_exit, dim3((a.B + 63) / 64), dim3(64), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace sx

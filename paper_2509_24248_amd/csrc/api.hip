@@ -1,0 +1,442 @@
+// C ABI of the SpecExit decode-round library: argument checks, workspace carving and the
+// order of kernel launches.  No arithmetic of the method lives here.
+#include "../../include/specexit.h"
+
+#include "kernels.hpp"
+
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+using namespace sx;
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int32_t fail(int32_t code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int32_t check_hip(hipError_t e, const char* what) {
+  if (e == hipSuccess) return SPECEXIT_OK;
+  return fail(SPECEXIT_ELAUNCH, "%s: %s", what, hipGetErrorString(e));
+}
+
+int num_cus() {
+  static int n = 0;
+  if (n == 0) {
+    int dev = 0;
+    hipDeviceProp_t p;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess)
+      n = p.multiProcessorCount;
+    if (n <= 0) n = 256;
+  }
+  return n;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
+
+struct Carver {
+  char* base;
+  size_t off = 0;
+  explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+  template <typename T> T* take(size_t bytes) {
+    T* r = reinterpret_cast<T*>(base ? base + off : nullptr);
+    off += align256(bytes);
+    return r;
+  }
+};
+
+bool dtype_ok(int32_t dt) { return dt == SPECEXIT_F32 || dt == SPECEXIT_BF16; }
+size_t esize(int32_t dt) { return dt == SPECEXIT_BF16 ? 2 : 4; }
+
+int32_t check_kv(const specexit_kv_view* kv, const char* who) {
+  if (!kv || kv->struct_size != sizeof(specexit_kv_view)) return fail(SPECEXIT_EINVAL, "%s: kv view missing or of another ABI size", who);
+  if (!dtype_ok(kv->dtype)) return fail(SPECEXIT_EINVAL, "%s: unknown kv dtype %d", who, kv->dtype);
+  if (!kv->k || !kv->v) return fail(SPECEXIT_EINVAL, "%s: kv pointers are null", who);
+  if (kv->head_dim != 64 && kv->head_dim != 128) return fail(SPECEXIT_EUNSUPPORTED, "%s: head_dim %d not in {64,128}", who, kv->head_dim);
+  if (kv->n_kv_heads < 1) return fail(SPECEXIT_EINVAL, "%s: n_kv_heads < 1", who);
+  if (kv->layout == SPECEXIT_KV_PAGED) {
+    if (!kv->page_table) return fail(SPECEXIT_EINVAL, "%s: paged layout without page_table", who);
+    if (kv->page_size < 16 || kv->page_size % 16) return fail(SPECEXIT_EUNSUPPORTED, "%s: page_size %d is not a multiple of 16", who, kv->page_size);
+    if (kv->max_pages_per_seq < 1 || kv->n_pages < 1) return fail(SPECEXIT_EINVAL, "%s: empty page pool", who);
+  } else if (kv->layout == SPECEXIT_KV_CONTIG) {
+    if (kv->l_max < 1) return fail(SPECEXIT_EINVAL, "%s: l_max < 1", who);
+  } else {
+    return fail(SPECEXIT_EINVAL, "%s: unknown kv layout %d", who, kv->layout);
+  }
+  return SPECEXIT_OK;
+}
+
+int32_t fill_attn(AttnArgs& a, const specexit_kv_view* kv, int32_t B, int32_t n_q, int32_t n_q_heads, const char* who) {
+  int32_t rc = check_kv(kv, who);
+  if (rc) return rc;
+  if (B < 1) return fail(SPECEXIT_EINVAL, "%s: B < 1", who);
+  if (n_q < 1 || n_q > SPECEXIT_MAX_NQ) return fail(SPECEXIT_EINVAL, "%s: n_q %d outside 1..64", who, n_q);
+  if (n_q_heads < 1 || n_q_heads % kv->n_kv_heads) return fail(SPECEXIT_EINVAL, "%s: n_q_heads %d is not a multiple of n_kv_heads %d", who, n_q_heads, kv->n_kv_heads);
+  if ((n_q_heads / kv->n_kv_heads) * n_q > 128) return fail(SPECEXIT_EUNSUPPORTED, "%s: more than 128 query rows per KV head", who);
+  memset(&a, 0, sizeof(a));
+  a.dtype = kv->dtype;
+  a.paged = kv->layout == SPECEXIT_KV_PAGED;
+  a.k = kv->k;
+  a.v = kv->v;
+  a.page_table = kv->page_table;
+  a.page_size = a.paged ? kv->page_size : 16;
+  a.max_pages = kv->max_pages_per_seq;
+  a.l_max = a.paged ? static_cast<int64_t>(kv->max_pages_per_seq) * kv->page_size : kv->l_max;
+  a.B = B;
+  a.n_q = n_q;
+  a.Hq = n_q_heads;
+  a.Hkv = kv->n_kv_heads;
+  a.d = kv->head_dim;
+  attn_plan(a, num_cus());
+  return SPECEXIT_OK;
+}
+
+// --------------------------------------------------------------------------- draft plan
+struct DraftPlan {
+  DraftDims dm;
+  bool mfma;
+  int B;
+  int Kmax;
+  GemmArgs fc, qkv, o, gu, down, head;
+  AttnArgs attn;
+  size_t partial_bytes;
+  int ntiles_head;
+};
+
+void plan_gemm(GemmArgs& g, int N, int K, int M, int planes, bool mfma, int V) {
+  memset(&g, 0, sizeof(g));
+  g.N = N;
+  g.K = K;
+  g.M = M;
+  g.planes = mfma ? planes : 1;
+  g.V = V;
+  g.nseg = 1;
+  g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = N;
+  choose_ksplit(g, mfma);
+}
+
+size_t partial_bytes_of(const GemmArgs& g, bool mfma) {
+  if (g.V >= 0 && mfma) return 0;
+  return static_cast<size_t>(g.ksplit) * g.M * g.planes * g.N * sizeof(float);
+}
+
+int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specexit_kv_view* kv, int32_t B) {
+  if (!d || d->struct_size != sizeof(specexit_model_desc)) return fail(SPECEXIT_EINVAL, "draft_step: model desc missing or of another ABI size");
+  if (!dtype_ok(d->dtype)) return fail(SPECEXIT_EINVAL, "draft_step: unknown dtype %d", d->dtype);
+  if (B < 1 || B > 64) return fail(SPECEXIT_EINVAL, "draft_step: B %d outside 1..64", B);
+  if (d->hidden < 64 || d->hidden % 64 || d->hidden > 8192) return fail(SPECEXIT_EUNSUPPORTED, "draft_step: hidden %d must be a multiple of 64 up to 8192", d->hidden);
+  if (d->intermediate < 64 || d->intermediate % 64) return fail(SPECEXIT_EUNSUPPORTED, "draft_step: intermediate %d must be a multiple of 64", d->intermediate);
+  if (d->vocab < 1) return fail(SPECEXIT_EINVAL, "draft_step: vocab < 1");
+  if (d->rem_activation < 0 || d->rem_activation > 2) return fail(SPECEXIT_EINVAL, "draft_step: rem_activation %d", d->rem_activation);
+  int32_t rc = fill_attn(p.attn, kv, B, 1, d->n_q_heads, "draft_step");
+  if (rc) return rc;
+  if (kv->dtype != d->dtype || kv->n_kv_heads != d->n_kv_heads || kv->head_dim != d->head_dim)
+    return fail(SPECEXIT_EINVAL, "draft_step: draft kv view does not match the model desc");
+  DraftDims& dm = p.dm;
+  dm.dtype = d->dtype; dm.D = d->hidden; dm.Hq = d->n_q_heads; dm.Hkv = d->n_kv_heads; dm.d = d->head_dim;
+  dm.I = d->intermediate; dm.V = d->vocab; dm.rms_eps = d->rms_eps; dm.rope_theta = d->rope_theta;
+  dm.rem_activation = d->rem_activation;
+  p.B = B;
+  const int D = dm.D, Hd = dm.Hq * dm.d, I = dm.I;
+  p.Kmax = 2 * D > Hd ? 2 * D : Hd;
+  if (I > p.Kmax) p.Kmax = I;
+  p.mfma = dm.dtype == SPECEXIT_BF16 && gemm_mfma_supported(B, 2, 2 * D) && gemm_mfma_supported(B, 2, D) &&
+           gemm_mfma_supported(B, 2, Hd) && gemm_mfma_supported(B, 2, I);
+  plan_gemm(p.fc, D, 2 * D, B, 1, p.mfma, -1);
+  plan_gemm(p.qkv, (dm.Hq + 2 * dm.Hkv) * dm.d, D, B, 2, p.mfma, -1);
+  p.qkv.nseg = 3;
+  p.qkv.seg_end[0] = Hd;
+  p.qkv.seg_end[1] = Hd + dm.Hkv * dm.d;
+  p.qkv.seg_end[2] = Hd + 2 * dm.Hkv * dm.d;
+  plan_gemm(p.o, D, Hd, B, 1, p.mfma, -1);
+  plan_gemm(p.gu, 2 * I, D, B, 2, p.mfma, -1);
+  p.gu.nseg = 2;
+  p.gu.seg_end[0] = I;
+  p.gu.seg_end[1] = p.gu.seg_end[2] = 2 * I;
+  plan_gemm(p.down, D, I, B, 2, p.mfma, -1);
+  plan_gemm(p.head, dm.V + 3, D, B, 2, p.mfma, dm.V);
+  p.head.n_extra = 3;
+  p.ntiles_head = gemm_ntiles(dm.V + 3);
+  size_t pb = 0;
+  const GemmArgs* all[6] = {&p.fc, &p.qkv, &p.o, &p.gu, &p.down, &p.head};
+  for (const GemmArgs* g : all) {
+    const size_t b = partial_bytes_of(*g, p.mfma);
+    if (b > pb) pb = b;
+  }
+  p.partial_bytes = pb;
+  return SPECEXIT_OK;
+}
+
+struct DraftBufs {
+  float* act;
+  uint4* apack;
+  float* partial;
+  float *x_buf, *a_buf;
+  void *q_buf, *attn_out;
+  void* attn_ws;
+  float* part_val;
+  int* part_idx;
+  int32_t* head_am;
+  float* extra;
+  size_t total;
+};
+
+DraftBufs carve_draft(const DraftPlan& p, void* ws) {
+  Carver c(ws);
+  DraftBufs b;
+  const size_t es = esize(p.dm.dtype);
+  b.act = c.take<float>(sizeof(float) * p.B * p.Kmax);
+  b.apack = c.take<uint4>(apack_bytes(p.B, 2, (p.Kmax + 127) / 128 * 128));
+  b.partial = c.take<float>(p.partial_bytes);
+  b.x_buf = c.take<float>(sizeof(float) * p.B * p.dm.D);
+  b.a_buf = c.take<float>(sizeof(float) * p.B * p.dm.D);
+  b.q_buf = c.take<char>(es * p.B * p.dm.Hq * p.dm.d);
+  b.attn_out = c.take<char>(es * p.B * p.dm.Hq * p.dm.d);
+  b.attn_ws = c.take<char>(attn_workspace_bytes(p.attn));
+  b.part_val = c.take<float>(sizeof(float) * p.B * p.ntiles_head);
+  b.part_idx = c.take<int>(sizeof(int) * p.B * p.ntiles_head);
+  b.head_am = c.take<int32_t>(sizeof(int32_t) * p.B);
+  b.extra = c.take<float>(sizeof(float) * p.B * 3);
+  b.total = c.off;
+  return b;
+}
+
+int32_t run_gemm(GemmArgs g, bool mfma, bool bf16, const void* w0, const void* w1, const void* w2,
+                 const DraftBufs& b, hipStream_t s, const char* what) {
+  g.w[0] = w0; g.w[1] = w1; g.w[2] = w2;
+  g.act = b.act;
+  g.apack = b.apack;
+  g.partial = b.partial;
+  g.part_val = b.part_val;
+  g.part_idx = b.part_idx;
+  g.extra_out = b.extra;
+  return check_hip(mfma ? launch_gemm_mfma(g, s) : launch_gemm_valu(g, bf16, s), what);
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* specexit_last_error(void) { return g_err; }
+uint32_t specexit_version(void) { return 0x00010000u; }
+
+size_t specexit_draft_step_workspace_bytes(const specexit_model_desc* desc, const specexit_kv_view* draft_kv, int32_t B) {
+  DraftPlan p;
+  if (make_draft_plan(p, desc, draft_kv, B)) return 0;
+  return carve_draft(p, nullptr).total;
+}
+
+int32_t specexit_draft_step(const specexit_model_desc* desc, const specexit_draft_weights* w,
+                            const specexit_kv_view* draft_kv, int32_t B, const int32_t* tok,
+                            const void* hidden_in, const int32_t* pos, void* hidden_out, int32_t* next_tok,
+                            float* sig_raw, float* sig, void* workspace, size_t workspace_bytes,
+                            uint32_t flags, void* stream) {
+  (void)flags;
+  DraftPlan p;
+  int32_t rc = make_draft_plan(p, desc, draft_kv, B);
+  if (rc) return rc;
+  if (!w || w->struct_size != sizeof(specexit_draft_weights)) return fail(SPECEXIT_EINVAL, "draft_step: weights missing or of another ABI size");
+  const void* ptrs[] = {w->embed, w->w_fc, w->ln_attn, w->ln_mlp, w->ln_final, w->w_q, w->w_k, w->w_v,
+                        w->w_o, w->w_gate, w->w_up, w->w_down, w->w_head, tok, hidden_in, pos, hidden_out,
+                        next_tok, sig_raw, sig};
+  for (const void* q : ptrs)
+    if (!q) return fail(SPECEXIT_EINVAL, "draft_step: a required pointer is null");
+  if (hidden_in == hidden_out) return fail(SPECEXIT_EINVAL, "draft_step: hidden_in and hidden_out alias");
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return fail(SPECEXIT_EWORKSPACE, "draft_step: workspace null or not 256-byte aligned");
+  const DraftBufs b = carve_draft(p, workspace);
+  if (workspace_bytes < b.total) return fail(SPECEXIT_EWORKSPACE, "draft_step: workspace %zu < %zu bytes", workspace_bytes, b.total);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const DraftDims& dm = p.dm;
+  const bool bf16 = dm.dtype == SPECEXIT_BF16;
+  const bool mf = p.mfma;
+  uint4* ap = mf ? b.apack : nullptr;
+  const int pp = mf ? 2 : 1;
+
+  // x = W_fc [embed[tok] ; hidden_in]
+  if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, tok, hidden_in, b.act, ap, s), "embed_concat"))) return rc;
+  if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
+  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.fc.ksplit, p.fc.planes, nullptr, w->ln_attn,
+                                         b.x_buf, nullptr, b.act, ap, pp, s), "norm attn"))) return rc;
+  // q, k, v; rotary; cache write; attention over the draft's own cache
+  if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
+  if ((rc = check_hip(launch_rope_kvwrite(dm, B, b.partial, p.qkv.ksplit, p.qkv.planes, pos, b.q_buf, p.attn.paged,
+                                          draft_kv->k, draft_kv->v, draft_kv->page_table, p.attn.page_size,
+                                          p.attn.max_pages, p.attn.l_max, s), "rope"))) return rc;
+  AttnArgs at = p.attn;
+  at.q = b.q_buf;
+  at.ctx_len = pos;
+  at.mask = nullptr;
+  at.scale = 1.0f / sqrtf(static_cast<float>(dm.d));
+  at.out = b.attn_out;
+  {
+    Carver c(b.attn_ws);
+    const size_t R = static_cast<size_t>(at.Hq / at.Hkv) * at.n_q;
+    const size_t units = static_cast<size_t>(at.B) * at.Hkv * at.nsplit;
+    at.part_o = c.take<float>(units * R * at.d * sizeof(float));
+    at.part_ml = c.take<float>(units * R * 2 * sizeof(float));
+  }
+  if ((rc = check_hip(launch_attn(at, s), "draft attention"))) return rc;
+  // a = x + W_o attn
+  if ((rc = check_hip(launch_pack_rows(b.attn_out, bf16, B, dm.Hq * dm.d, ap, b.act, s), "pack attn"))) return rc;
+  if ((rc = run_gemm(p.o, mf, bf16, w->w_o, nullptr, nullptr, b, s, "gemm o"))) return rc;
+  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.o.ksplit, p.o.planes, b.x_buf, w->ln_mlp,
+                                         b.a_buf, nullptr, b.act, ap, pp, s), "norm mlp"))) return rc;
+  // y = a + W_down (silu(W_gate m) * W_up m)
+  if ((rc = run_gemm(p.gu, mf, bf16, w->w_gate, w->w_up, nullptr, b, s, "gemm gate/up"))) return rc;
+  if ((rc = check_hip(launch_silu_mul(dm, B, b.partial, p.gu.ksplit, p.gu.planes, b.act, ap, pp, s), "silu"))) return rc;
+  if ((rc = run_gemm(p.down, mf, bf16, w->w_down, nullptr, nullptr, b, s, "gemm down"))) return rc;
+  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.down.ksplit, p.down.planes, b.a_buf, w->ln_final,
+                                         nullptr, hidden_out, b.act, ap, pp, s), "norm final"))) return rc;
+  // widened head (Eq. 1): argmax over the vocabulary rows, three signal rows on the side
+  if ((rc = run_gemm(p.head, mf, bf16, w->w_head, nullptr, nullptr, b, s, "gemm head"))) return rc;
+  if (mf) {
+    if ((rc = check_hip(launch_argmax_finalize(b.part_val, b.part_idx, p.ntiles_head, B, b.head_am, nullptr, s), "argmax finalize"))) return rc;
+  } else {
+    if ((rc = check_hip(launch_argmax_rows(b.partial, B, dm.V + 3, dm.V, 3, b.head_am, nullptr, b.extra, nullptr, s), "argmax rows"))) return rc;
+  }
+  return check_hip(launch_head_finalize(dm, B, b.head_am, b.extra, next_tok, sig_raw, sig, s), "head finalize");
+}
+
+size_t specexit_verify_attn_workspace_bytes(const specexit_kv_view* kv, int32_t B, int32_t n_q, int32_t n_q_heads) {
+  AttnArgs a;
+  if (fill_attn(a, kv, B, n_q, n_q_heads, "verify_attn")) return 0;
+  return attn_workspace_bytes(a);
+}
+
+int32_t specexit_verify_attn(const specexit_kv_view* kv, int32_t B, int32_t n_q, int32_t n_q_heads, const void* q,
+                             const int32_t* ctx_len, const uint64_t* mask, float scale, void* out,
+                             void* workspace, size_t workspace_bytes, uint32_t flags, void* stream) {
+  (void)flags;
+  AttnArgs a;
+  int32_t rc = fill_attn(a, kv, B, n_q, n_q_heads, "verify_attn");
+  if (rc) return rc;
+  if (!q || !ctx_len || !out) return fail(SPECEXIT_EINVAL, "verify_attn: a required pointer is null");
+  if (!(scale > 0.f)) return fail(SPECEXIT_EINVAL, "verify_attn: scale must be positive");
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return fail(SPECEXIT_EWORKSPACE, "verify_attn: workspace null or not 256-byte aligned");
+  const size_t need = attn_workspace_bytes(a);
+  if (workspace_bytes < need) return fail(SPECEXIT_EWORKSPACE, "verify_attn: workspace %zu < %zu bytes", workspace_bytes, need);
+  a.q = q;
+  a.ctx_len = ctx_len;
+  a.mask = mask;
+  a.scale = scale;
+  a.out = out;
+  Carver c(workspace);
+  const size_t R = static_cast<size_t>(a.Hq / a.Hkv) * a.n_q;
+  const size_t units = static_cast<size_t>(a.B) * a.Hkv * a.nsplit;
+  a.part_o = c.take<float>(units * R * a.d * sizeof(float));
+  a.part_ml = c.take<float>(units * R * 2 * sizeof(float));
+  return check_hip(launch_attn(a, static_cast<hipStream_t>(stream)), "verify_attn");
+}
+
+namespace {
+struct HeadPlan {
+  bool mfma;
+  GemmArgs g;
+  int ntiles;
+  size_t act_bytes, apack_bytes_, partial_bytes, pv_bytes;
+};
+int32_t make_head_plan(HeadPlan& h, int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra) {
+  if (!dtype_ok(dtype)) return fail(SPECEXIT_EINVAL, "lmhead_argmax: unknown dtype %d", dtype);
+  if (M < 1 || M > 144) return fail(SPECEXIT_EINVAL, "lmhead_argmax: M %d outside 1..144", M);
+  if (D < 8 || D % 8) return fail(SPECEXIT_EUNSUPPORTED, "lmhead_argmax: D %d must be a multiple of 8", D);
+  if (V < 1 || n_extra < 0 || n_extra > 16) return fail(SPECEXIT_EINVAL, "lmhead_argmax: bad V or n_extra");
+  h.mfma = dtype == SPECEXIT_BF16 && gemm_mfma_supported(M, 1, D);
+  plan_gemm(h.g, V + n_extra, D, M, 1, h.mfma, V);
+  h.g.n_extra = n_extra;
+  h.ntiles = gemm_ntiles(V + n_extra);
+  h.act_bytes = (!h.mfma && dtype == SPECEXIT_BF16) ? sizeof(float) * M * D : 0;
+  h.apack_bytes_ = h.mfma ? apack_bytes(M, 1, D) : 0;
+  h.partial_bytes = h.mfma ? 0 : sizeof(float) * M * (static_cast<size_t>(V) + n_extra);
+  h.pv_bytes = h.mfma ? sizeof(float) * M * h.ntiles : 0;
+  return SPECEXIT_OK;
+}
+}  // namespace
+
+size_t specexit_lmhead_argmax_workspace_bytes(int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra) {
+  HeadPlan h;
+  if (make_head_plan(h, dtype, M, D, V, n_extra)) return 0;
+  size_t t = align256(h.act_bytes) + align256(h.apack_bytes_) + align256(h.partial_bytes) + 2 * align256(h.pv_bytes);
+  return t ? t : 256;
+}
+
+int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra, const void* hidden,
+                               const void* w, int32_t* argmax, float* max_logit, float* extra_out,
+                               float* logits_dbg, void* workspace, size_t workspace_bytes, uint32_t flags,
+                               void* stream) {
+  (void)flags;
+  HeadPlan h;
+  int32_t rc = make_head_plan(h, dtype, M, D, V, n_extra);
+  if (rc) return rc;
+  if (!hidden || !w || !argmax) return fail(SPECEXIT_EINVAL, "lmhead_argmax: a required pointer is null");
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return fail(SPECEXIT_EWORKSPACE, "lmhead_argmax: workspace null or not 256-byte aligned");
+  const size_t need = specexit_lmhead_argmax_workspace_bytes(dtype, M, D, V, n_extra);
+  if (workspace_bytes < need) return fail(SPECEXIT_EWORKSPACE, "lmhead_argmax: workspace %zu < %zu bytes", workspace_bytes, need);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  Carver c(workspace);
+  float* act = c.take<float>(h.act_bytes);
+  uint4* ap = c.take<uint4>(h.apack_bytes_);
+  float* partial = c.take<float>(h.partial_bytes);
+  float* pv = c.take<float>(h.pv_bytes);
+  int* pi = c.take<int>(h.pv_bytes);
+  GemmArgs g = h.g;
+  g.w[0] = w;
+  g.extra_out = n_extra ? extra_out : nullptr;
+  g.logits_dbg = logits_dbg;
+  const bool bf16 = dtype == SPECEXIT_BF16;
+  if (h.mfma) {
+    if ((rc = check_hip(launch_pack_rows(hidden, true, M, D, ap, nullptr, s), "pack hidden"))) return rc;
+    g.apack = ap;
+    g.part_val = pv;
+    g.part_idx = pi;
+    if ((rc = check_hip(launch_gemm_mfma(g, s), "gemm lm head"))) return rc;
+    return check_hip(launch_argmax_finalize(pv, pi, h.ntiles, M, argmax, max_logit, s), "argmax finalize");
+  }
+  if (bf16) {
+    if ((rc = check_hip(launch_pack_rows(hidden, true, M, D, nullptr, act, s), "unpack hidden"))) return rc;
+    g.act = act;
+  } else {
+    g.act = static_cast<const float*>(hidden);
+  }
+  g.partial = partial;
+  if ((rc = check_hip(launch_gemm_valu(g, bf16, s), "gemv lm head"))) return rc;
+  return check_hip(launch_argmax_rows(partial, M, V + n_extra, V, n_extra, argmax, max_logit,
+                                      n_extra ? extra_out : nullptr, logits_dbg, s), "argmax rows");
+}
+
+int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_q, const int32_t* block_tok,
+                             const int32_t* parent, const int32_t* target_argmax, const float* sig,
+                             const int32_t* ctx_len, const int32_t* split_tok, int32_t S, float* ewma,
+                             int32_t* n_obs, int32_t* is_thinking, int32_t* accept_len, int32_t* accept_path,
+                             int32_t* recover_tok, int32_t* last_node, int32_t* exit_flag, int32_t* new_ctx_len,
+                             uint32_t flags, void* stream) {
+  (void)flags;
+  if (!cfg || cfg->struct_size != sizeof(specexit_exit_cfg)) return fail(SPECEXIT_EINVAL, "accept_exit: cfg missing or of another ABI size");
+  if (B < 1) return fail(SPECEXIT_EINVAL, "accept_exit: B < 1");
+  if (n_q < 1 || n_q > SPECEXIT_MAX_NQ) return fail(SPECEXIT_EINVAL, "accept_exit: n_q %d outside 1..64", n_q);
+  if (S < 0 || (S > 0 && !split_tok)) return fail(SPECEXIT_EINVAL, "accept_exit: split token set missing");
+  if (!(cfg->alpha >= 0.f && cfg->alpha <= 1.f)) return fail(SPECEXIT_EINVAL, "accept_exit: alpha outside [0,1]");
+  if (cfg->smoother < 0 || cfg->smoother > 1) return fail(SPECEXIT_EUNSUPPORTED, "accept_exit: smoother %d", cfg->smoother);
+  const void* ptrs[] = {block_tok, target_argmax, sig, ctx_len, ewma, n_obs, is_thinking, accept_len,
+                        accept_path, recover_tok, last_node, exit_flag, new_ctx_len};
+  for (const void* q : ptrs)
+    if (!q) return fail(SPECEXIT_EINVAL, "accept_exit: a required pointer is null");
+  ExitArgs a;
+  a.alpha = cfg->alpha; a.thr_conf = cfg->thr_conf; a.thr_prog = cfg->thr_prog; a.thr_rem = cfg->thr_rem;
+  a.signal_mask = cfg->signal_mask; a.smoother = cfg->smoother; a.split_pick = cfg->split_pick;
+  a.check_root = cfg->check_root; a.stop_think_token = cfg->stop_think_token;
+  a.B = B; a.n_q = n_q; a.S = S;
+  a.block_tok = block_tok; a.parent = parent; a.target_argmax = target_argmax; a.sig = sig;
+  a.ctx_len = ctx_len; a.split_tok = split_tok; a.ewma = ewma; a.n_obs = n_obs; a.is_thinking = is_thinking;
+  a.accept_len = accept_len; a.accept_path = accept_path; a.recover_tok = recover_tok; a.last_node = last_node;
+  a.exit_flag = exit_flag; a.new_ctx_len = new_ctx_len;
+  return check_hip(launch_accept_exit(a, static_cast<hipStream_t>(stream)), "accept_exit");
+}
+
+}  // extern "C"

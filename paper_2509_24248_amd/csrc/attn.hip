@@ -1,0 +1,254 @@
+// Verification attention (Alg. 1, "forward through M_t with tree attention"): the draft
+// block's n_q queries of every head attend to the whole cached context plus the block
+// entries their ancestor mask allows.  The KV cache is read once: all G * n_q query rows
+// that share a KV head are processed together, the cache length is cut into chunks that
+// run as independent workgroups (each keeps an online softmax), and a second kernel
+// merges the chunks' (max, sum, output) triples exactly.
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sx {
+
+namespace {
+
+constexpr int kTK = 32;  // keys per tile of the ALU kernel
+
+template <typename T>
+__device__ __forceinline__ const T* kv_row(const AttnArgs& a, const void* pool, int b, int g, int64_t p) {
+  const T* base = static_cast<const T*>(pool);
+  if (a.paged) {
+    const int page = a.page_table[static_cast<size_t>(b) * a.max_pages + p / a.page_size];
+    return base + ((static_cast<size_t>(page) * a.Hkv + g) * a.page_size + p % a.page_size) * a.d;
+  }
+  return base + ((static_cast<size_t>(b) * a.Hkv + g) * a.l_max + p) * a.d;
+}
+
+// Plain-ALU kernel, any storage type: the reference path for fp32 caches.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
+  extern __shared__ float smem[];
+  const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  const int G = a.Hq / a.Hkv;
+  const int R = G * a.n_q;
+  const int L = a.ctx_len[b];
+  const int total = L + a.n_q;
+  const int s0 = split * a.chunk;
+  if (s0 >= total) return;
+  const int s1 = min(total, s0 + a.chunk);
+  constexpr int DP = D + 4;
+  float* Qs = smem;                 // [R][D]
+  float* Ks = Qs + R * D;           // [kTK][DP]
+  float* Vs = Ks + kTK * DP;        // [kTK][DP]
+  float* Ss = Vs + kTK * DP;        // [R][kTK]
+  float* Ms = Ss + R * kTK;         // [R] running max
+  float* Ls = Ms + R;               // [R] running sum
+  float* As = Ls + R;               // [R] rescale of this tile
+  const int tid = threadIdx.x;
+
+  for (int idx = tid; idx < R * D; idx += 256) {
+    const int r = idx / D, c = idx % D;
+    const int i = r / G, hh = r % G;
+    const T* qp = static_cast<const T*>(a.q) + ((static_cast<size_t>(b) * a.n_q + i) * a.Hq + g * G + hh) * D;
+    Qs[idx] = Elem<T>::load(qp + c);
+  }
+  for (int r = tid; r < R; r += 256) { Ms[r] = -INFINITY; Ls[r] = 0.f; }
+
+  constexpr int C4 = D / 4;               // float4 columns
+  constexpr int RSTEP = 256 / C4;         // rows covered per pass
+  constexpr int MAXU = (128 + RSTEP - 1) / RSTEP;
+  const int c4 = tid % C4, r0 = tid / C4;
+  float4 o[MAXU];
+#pragma unroll
+  for (int u = 0; u < MAXU; ++u) o[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+  __syncthreads();
+
+  for (int t0 = s0; t0 < s1; t0 += kTK) {
+    // stage K and V rows of this tile as fp32
+    for (int idx = tid; idx < kTK * (D / Elem<T>::kPer16B); idx += 256) {
+      constexpr int VPR = D / Elem<T>::kPer16B;
+      const int j = idx / VPR, vc = idx % VPR;
+      const int p = t0 + j;
+      float kf[8], vf[8];
+      if (p < s1) {
+        const uint4 kraw = reinterpret_cast<const uint4*>(kv_row<T>(a, a.k, b, g, p))[vc];
+        const uint4 vraw = reinterpret_cast<const uint4*>(kv_row<T>(a, a.v, b, g, p))[vc];
+        if (Elem<T>::kPer16B == 8) {
+          unpack16(kraw, kf);
+          unpack16(vraw, vf);
+        } else {
+          kf[0] = __uint_as_float(kraw.x); kf[1] = __uint_as_float(kraw.y);
+          kf[2] = __uint_as_float(kraw.z); kf[3] = __uint_as_float(kraw.w);
+          vf[0] = __uint_as_float(vraw.x); vf[1] = __uint_as_float(vraw.y);
+          vf[2] = __uint_as_float(vraw.z); vf[3] = __uint_as_float(vraw.w);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { kf[e] = 0.f; vf[e] = 0.f; }
+      }
+#pragma unroll
+      for (int e = 0; e < Elem<T>::kPer16B; ++e) {
+        Ks[j * DP + vc * Elem<T>::kPer16B + e] = kf[e];
+        Vs[j * DP + vc * Elem<T>::kPer16B + e] = vf[e];
+      }
+    }
+    __syncthreads();
+    // scores with the block mask applied
+    for (int idx = tid; idx < R * kTK; idx += 256) {
+      const int r = idx / kTK, j = idx % kTK;
+      const int p = t0 + j;
+      bool vis = p < s1;
+      if (vis && p >= L) {
+        const int i = r / G;
+        const uint64_t row = a.mask ? a.mask[static_cast<size_t>(b) * a.n_q + i] : ((2ull << i) - 1ull);
+        vis = (row >> (p - L)) & 1ull;
+      }
+      float acc = 0.f;
+      if (vis) {
+        const float4* qv = reinterpret_cast<const float4*>(Qs + r * D);
+        const float4* kv = reinterpret_cast<const float4*>(Ks + j * DP);
+#pragma unroll 8
+        for (int c = 0; c < C4; ++c) {
+          const float4 x = qv[c], y = kv[c];
+          acc = fmaf(x.x, y.x, acc); acc = fmaf(x.y, y.y, acc);
+          acc = fmaf(x.z, y.z, acc); acc = fmaf(x.w, y.w, acc);
+        }
+      }
+      Ss[idx] = vis ? acc * a.scale : -INFINITY;
+    }
+    __syncthreads();
+    // online softmax bookkeeping, one thread per row
+    for (int r = tid; r < R; r += 256) {
+      float tmax = -INFINITY;
+      for (int j = 0; j < kTK; ++j) tmax = fmaxf(tmax, Ss[r * kTK + j]);
+      const float m_old = Ms[r];
+      const float m_new = fmaxf(m_old, tmax);
+      float alpha = 1.f, sum = 0.f;
+      if (m_new == -INFINITY) {
+        for (int j = 0; j < kTK; ++j) Ss[r * kTK + j] = 0.f;
+      } else {
+        alpha = (m_old == -INFINITY) ? 0.f : expf(m_old - m_new);
+        for (int j = 0; j < kTK; ++j) {
+          const float pj = expf(Ss[r * kTK + j] - m_new);  // exp(-inf) = 0 for masked keys
+          Ss[r * kTK + j] = pj;
+          sum += pj;
+        }
+      }
+      Ms[r] = m_new;
+      Ls[r] = Ls[r] * alpha + sum;
+      As[r] = alpha;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < MAXU; ++u) {
+      const int r = r0 + u * RSTEP;
+      if (r < R) {
+        const float al = As[r];
+        float4 acc = make_float4(o[u].x * al, o[u].y * al, o[u].z * al, o[u].w * al);
+        for (int j = 0; j < kTK; ++j) {
+          const float pj = Ss[r * kTK + j];
+          const float4 vv = *reinterpret_cast<const float4*>(Vs + j * DP + c4 * 4);
+          acc.x = fmaf(pj, vv.x, acc.x); acc.y = fmaf(pj, vv.y, acc.y);
+          acc.z = fmaf(pj, vv.z, acc.z); acc.w = fmaf(pj, vv.w, acc.w);
+        }
+        o[u] = acc;
+      }
+    }
+    __syncthreads();
+  }
+  const size_t unit = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit + split;
+#pragma unroll
+  for (int u = 0; u < MAXU; ++u) {
+    const int r = r0 + u * RSTEP;
+    if (r < R) *reinterpret_cast<float4*>(a.part_o + (unit * R + r) * D + c4 * 4) = o[u];
+  }
+  for (int r = tid; r < R; r += 256) {
+    a.part_ml[(unit * R + r) * 2 + 0] = Ms[r];
+    a.part_ml[(unit * R + r) * 2 + 1] = Ls[r];
+  }
+}
+
+// Merge the chunks of one (sequence, query, head): exact log-sum-exp combination.
+template <typename T>
+__global__ void k_attn_combine(const AttnArgs a) {
+  const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
+  const int c = threadIdx.x;  // < d
+  const int G = a.Hq / a.Hkv;
+  const int R = G * a.n_q;
+  const int g = h / G, r = i * G + h % G;
+  const int total = a.ctx_len[b] + a.n_q;
+  const int nact = (total + a.chunk - 1) / a.chunk;
+  const size_t unit0 = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit;
+  float mmax = -INFINITY;
+  for (int s = 0; s < nact; ++s) mmax = fmaxf(mmax, a.part_ml[((unit0 + s) * R + r) * 2]);
+  float den = 0.f, num = 0.f;
+  for (int s = 0; s < nact; ++s) {
+    const float ms = a.part_ml[((unit0 + s) * R + r) * 2];
+    if (ms == -INFINITY) continue;
+    const float w = expf(ms - mmax);
+    den = fmaf(w, a.part_ml[((unit0 + s) * R + r) * 2 + 1], den);
+    num = fmaf(w, a.part_o[((unit0 + s) * R + r) * a.d + c], num);
+  }
+  T* dst = static_cast<T*>(a.out) + ((static_cast<size_t>(b) * a.n_q + i) * a.Hq + h) * a.d;
+  Elem<T>::store(dst + c, num / den);
+}
+
+size_t valu_smem_bytes(const AttnArgs& a) {
+  const int R = (a.Hq / a.Hkv) * a.n_q;
+  return sizeof(float) * (static_cast<size_t>(R) * a.d + 2 * kTK * (a.d + 4) + static_cast<size_t>(R) * kTK + 3 * R);
+}
+
+template <typename T, int D>
+hipError_t launch_valu(const AttnArgs& a, hipStream_t s) {
+  const size_t smem = valu_smem_bytes(a);
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_split_valu<T, D>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((k_attn_split_valu<T, D>), dim3(a.nsplit, a.Hkv, a.B), dim3(256), smem, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+void attn_plan(AttnArgs& a, int num_cus) {
+  // chunk of the cache length handled by one workgroup: enough workgroups to cover the
+  // chip about twice when every sequence is at its longest, never below 128 keys
+  const int64_t units = static_cast<int64_t>(a.B) * a.Hkv;
+  const int64_t lmax = a.l_max;
+  int64_t chunk = (units * lmax + 2 * num_cus - 1) / (2 * num_cus);
+  chunk = ((chunk + 127) / 128) * 128;
+  if (chunk < 128) chunk = 128;
+  a.chunk = static_cast<int>(chunk);
+  a.nsplit = static_cast<int>((lmax + chunk - 1) / chunk);
+  if (a.nsplit < 1) a.nsplit = 1;
+}
+
+size_t attn_workspace_bytes(const AttnArgs& a) {
+  const size_t R = static_cast<size_t>(a.Hq / a.Hkv) * a.n_q;
+  const size_t units = static_cast<size_t>(a.B) * a.Hkv * a.nsplit;
+  size_t o = units * R * a.d * sizeof(float);
+  o = (o + 255) & ~static_cast<size_t>(255);
+  size_t ml = units * R * 2 * sizeof(float);
+  ml = (ml + 255) & ~static_cast<size_t>(255);
+  return o + ml;
+}
+
+hipError_t launch_attn(const AttnArgs& a, hipStream_t s) {
+  hipError_t e;
+  if (a.dtype == 1) {
+    e = a.d == 128 ? launch_valu<bf16_t, 128>(a, s) : launch_valu<bf16_t, 64>(a, s);
+  } else {
+    e = a.d == 128 ? launch_valu<float, 128>(a, s) : launch_valu<float, 64>(a, s);
+  }
+  if (e != hipSuccess) return e;
+  if (a.dtype == 1)
+    hipLaunchKernelGGL(k_attn_combine<bf16_t>, dim3(a.Hq, a.n_q, a.B), dim3(a.d), 0, s, a);
+  else
+    hipLaunchKernelGGL(k_attn_combine<float>, dim3(a.Hq, a.n_q, a.B), dim3(a.d), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace sx

@@ -1,0 +1,281 @@
+// Row-wise glue of the draft step (Sec. 3.1; Alg. 1 first loop line): everything between
+// the weight-streaming GEMMs.  Each kernel reduces the split-K partial sums of the GEMM
+// before it, applies the layer's elementwise math in fp32 and emits the next GEMM's
+// activations, both as an fp32 row (ALU GEMM path) and as packed bf16 MFMA fragments
+// (hi part, optionally plus the bf16 rounding remainder so fp32 activations lose nothing).
+#include "common.hpp"
+#include "kernels.hpp"
+
+namespace sx {
+
+namespace {
+
+constexpr int kMaxGroups = 4;  // 8-element groups per thread: rows up to 4*256*8 = 8192 wide
+
+__device__ __forceinline__ float block_sum_256(float v, float* sh) {
+  v = wave_sum(v);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  const float r = sh[0] + sh[1] + sh[2] + sh[3];
+  __syncthreads();
+  return r;
+}
+
+// write 8 consecutive activations of row m starting at k = 8 * g8 into the fragments
+__device__ __forceinline__ void pack_store(uint4* apack, int MT, int planes, int m, int g8,
+                                           const float (&f)[8]) {
+  const int s = g8 >> 2, q = g8 & 3;
+  uint32_t hi[4], lo[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const bf16_t h0 = f32_to_bf16(f[2 * e]), h1 = f32_to_bf16(f[2 * e + 1]);
+    hi[e] = static_cast<uint32_t>(h0) | (static_cast<uint32_t>(h1) << 16);
+    const bf16_t l0 = f32_to_bf16(f[2 * e] - bf16_to_f32(h0));
+    const bf16_t l1 = f32_to_bf16(f[2 * e + 1] - bf16_to_f32(h1));
+    lo[e] = static_cast<uint32_t>(l0) | (static_cast<uint32_t>(l1) << 16);
+  }
+  const int v = m * planes;
+  apack[(static_cast<size_t>(s) * MT + (v >> 4)) * 64 + (v & 15) + 16 * q] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+  if (planes == 2) {
+    const int v1 = v + 1;
+    apack[(static_cast<size_t>(s) * MT + (v1 >> 4)) * 64 + (v1 & 15) + 16 * q] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+  }
+}
+
+// sum over split-K ranges and planes of 8 consecutive outputs of row b
+__device__ __forceinline__ void gather_partial(const float* partial, int nslices, int planes, int B,
+                                               int N, int b, int n, float (&f)[8]) {
+  const int Mv = B * planes;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) f[e] = 0.f;
+  for (int ks = 0; ks < nslices; ++ks) {
+    for (int p = 0; p < planes; ++p) {
+      const float4* src = reinterpret_cast<const float4*>(
+          partial + (static_cast<size_t>(ks) * Mv + b * planes + p) * N + n);
+      const float4 a = src[0], c = src[1];
+      f[0] += a.x; f[1] += a.y; f[2] += a.z; f[3] += a.w;
+      f[4] += c.x; f[5] += c.y; f[6] += c.z; f[7] += c.w;
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_embed_concat(int D, const T* __restrict__ embed,
+                                                      const int32_t* __restrict__ tok,
+                                                      const T* __restrict__ hidden_in,
+                                                      float* __restrict__ act, uint4* __restrict__ apack,
+                                                      int MT) {
+  const int b = blockIdx.x;
+  const T* e = embed + static_cast<size_t>(tok[b]) * D;
+  const T* h = hidden_in + static_cast<size_t>(b) * D;
+  for (int g8 = threadIdx.x; g8 < 2 * D / 8; g8 += 256) {
+    const int k = g8 * 8;
+    const T* src = k < D ? e + k : h + (k - D);
+    float f[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = Elem<T>::load(src + i);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) act[static_cast<size_t>(b) * 2 * D + k + i] = f[i];
+    if (apack) pack_store(apack, MT, 1, b, g8, f);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_reduce_norm(int B, int N, const float* __restrict__ partial,
+                                                     int nslices, int planes,
+                                                     const float* __restrict__ residual,
+                                                     const T* __restrict__ gain, float eps,
+                                                     float* __restrict__ sum_out, T* __restrict__ hidden_out,
+                                                     float* __restrict__ act, uint4* __restrict__ apack,
+                                                     int MT, int pack_planes) {
+  __shared__ float sh[4];
+  const int b = blockIdx.x;
+  float vals[kMaxGroups][8];
+  float ssq = 0.f;
+#pragma unroll
+  for (int it = 0; it < kMaxGroups; ++it) {
+    const int g8 = threadIdx.x + it * 256;
+    if (g8 < N / 8) {
+      float f[8];
+      gather_partial(partial, nslices, planes, B, N, b, g8 * 8, f);
+      if (residual) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] += residual[static_cast<size_t>(b) * N + g8 * 8 + e];
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        vals[it][e] = f[e];
+        ssq = fmaf(f[e], f[e], ssq);
+        if (sum_out) sum_out[static_cast<size_t>(b) * N + g8 * 8 + e] = f[e];
+        if (hidden_out) Elem<T>::store(hidden_out + static_cast<size_t>(b) * N + g8 * 8 + e, f[e]);
+      }
+    }
+  }
+  const float tot = block_sum_256(ssq, sh);
+  const float rinv = 1.0f / sqrtf(tot / static_cast<float>(N) + eps);
+#pragma unroll
+  for (int it = 0; it < kMaxGroups; ++it) {
+    const int g8 = threadIdx.x + it * 256;
+    if (g8 < N / 8) {
+      float f[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) f[e] = vals[it][e] * rinv * Elem<T>::load(gain + g8 * 8 + e);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) act[static_cast<size_t>(b) * N + g8 * 8 + e] = f[e];
+      if (apack) pack_store(apack, MT, pack_planes, b, g8, f);
+    }
+  }
+}
+
+template <typename T>
+__global__ void k_rope_kvwrite(int B, int Hq, int Hkv, int d, const float* __restrict__ partial,
+                               int nslices, int planes, const int32_t* __restrict__ pos, float theta,
+                               T* __restrict__ q_out, int paged, T* __restrict__ kc, T* __restrict__ vc,
+                               const int32_t* __restrict__ page_table, int page_size, int max_pages,
+                               int64_t l_max) {
+  const int b = blockIdx.x, hh = blockIdx.y, c = threadIdx.x;  // c in [0, d/2)
+  const int N = (Hq + 2 * Hkv) * d;
+  const int Mv = B * planes;
+  const int half = d >> 1;
+  float x1 = 0.f, x2 = 0.f;
+  for (int ks = 0; ks < nslices; ++ks)
+    for (int p = 0; p < planes; ++p) {
+      const float* src = partial + (static_cast<size_t>(ks) * Mv + b * planes + p) * N + hh * d;
+      x1 += src[c];
+      x2 += src[c + half];
+    }
+  const int ps = pos[b];
+  if (hh < Hq + Hkv) {
+    // rotary embedding, pairing (c, c + d/2); the angle is formed in double so that long
+    // positions keep their phase
+    const double inv = pow(static_cast<double>(theta), -2.0 * c / d);
+    const double ang = static_cast<double>(ps) * inv;
+    const float cs = static_cast<float>(cos(ang)), sn = static_cast<float>(sin(ang));
+    const float r1 = x1 * cs - x2 * sn;
+    const float r2 = x2 * cs + x1 * sn;
+    x1 = r1;
+    x2 = r2;
+  }
+  if (hh < Hq) {
+    T* dst = q_out + (static_cast<size_t>(b) * Hq + hh) * d;
+    Elem<T>::store(dst + c, x1);
+    Elem<T>::store(dst + c + half, x2);
+    return;
+  }
+  const bool is_k = hh < Hq + Hkv;
+  const int h = is_k ? hh - Hq : hh - Hq - Hkv;
+  size_t off;
+  if (paged) {
+    const int page = page_table[static_cast<size_t>(b) * max_pages + ps / page_size];
+    off = ((static_cast<size_t>(page) * Hkv + h) * page_size + ps % page_size) * d;
+  } else {
+    off = ((static_cast<size_t>(b) * Hkv + h) * l_max + ps) * d;
+  }
+  T* dst = (is_k ? kc : vc) + off;
+  Elem<T>::store(dst + c, x1);
+  Elem<T>::store(dst + c + half, x2);
+}
+
+__global__ __launch_bounds__(256) void k_silu_mul(int B, int I, const float* __restrict__ partial,
+                                                  int nslices, int planes, float* __restrict__ act,
+                                                  uint4* __restrict__ apack, int MT, int pack_planes) {
+  const int b = blockIdx.x;
+  for (int g8 = blockIdx.y * 256 + threadIdx.x; g8 < I / 8; g8 += 256 * gridDim.y) {
+    float gt[8], up[8], f[8];
+    gather_partial(partial, nslices, planes, B, 2 * I, b, g8 * 8, gt);
+    gather_partial(partial, nslices, planes, B, 2 * I, b, I + g8 * 8, up);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) f[e] = gt[e] * sigmoidf_(gt[e]) * up[e];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) act[static_cast<size_t>(b) * I + g8 * 8 + e] = f[e];
+    if (apack) pack_store(apack, MT, pack_planes, b, g8, f);
+  }
+}
+
+__global__ void k_head_finalize(int B, int rem_activation, const int32_t* __restrict__ argmax_in,
+                                const float* __restrict__ extra, int32_t* __restrict__ next_tok,
+                                float* __restrict__ sig_raw, float* __restrict__ sig) {
+  const int b = blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= B) return;
+  next_tok[b] = argmax_in[b];
+  const float zc = extra[b * 3 + 0], zp = extra[b * 3 + 1], zr = extra[b * 3 + 2];
+  sig_raw[b * 3 + 0] = zc;
+  sig_raw[b * 3 + 1] = zp;
+  sig_raw[b * 3 + 2] = zr;
+  // confidence and progress pass through a sigmoid (Eqs. 3-4); the remaining-length head
+  // regresses log(1 + r) (Eq. 5), so r = expm1(z), floored at zero
+  sig[b * 3 + 0] = sigmoidf_(zc);
+  sig[b * 3 + 1] = sigmoidf_(zp);
+  float r;
+  if (rem_activation == 0)
+    r = fmaxf(0.f, expm1f(zr));
+  else if (rem_activation == 1)
+    r = sigmoidf_(zr);
+  else
+    r = zr;
+  sig[b * 3 + 2] = r;
+}
+
+}  // namespace
+
+hipError_t launch_embed_concat(const DraftDims& dm, int B, const void* embed, const int32_t* tok,
+                               const void* hidden_in, float* act, uint4* apack, hipStream_t s) {
+  const int MT = gemm_mt(B, 1);
+  if (dm.dtype == 1)
+    hipLaunchKernelGGL(k_embed_concat<bf16_t>, dim3(B), dim3(256), 0, s, dm.D, static_cast<const bf16_t*>(embed),
+                       tok, static_cast<const bf16_t*>(hidden_in), act, apack, MT);
+  else
+    hipLaunchKernelGGL(k_embed_concat<float>, dim3(B), dim3(256), 0, s, dm.D, static_cast<const float*>(embed),
+                       tok, static_cast<const float*>(hidden_in), act, apack, MT);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* partial, int nslices,
+                              int planes, const float* residual, const void* gain, float* sum_out,
+                              void* hidden_out, float* act, uint4* apack, int pack_planes,
+                              hipStream_t s) {
+  const int MT = gemm_mt(B, pack_planes);
+  if (dm.dtype == 1)
+    hipLaunchKernelGGL(k_reduce_norm<bf16_t>, dim3(B), dim3(256), 0, s, B, N, partial, nslices, planes, residual,
+                       static_cast<const bf16_t*>(gain), dm.rms_eps, sum_out, static_cast<bf16_t*>(hidden_out), act,
+                       apack, MT, pack_planes);
+  else
+    hipLaunchKernelGGL(k_reduce_norm<float>, dim3(B), dim3(256), 0, s, B, N, partial, nslices, planes, residual,
+                       static_cast<const float*>(gain), dm.rms_eps, sum_out, static_cast<float*>(hidden_out), act,
+                       apack, MT, pack_planes);
+  return hipGetLastError();
+}
+
+hipError_t launch_rope_kvwrite(const DraftDims& dm, int B, const float* partial, int nslices,
+                               int planes, const int32_t* pos, void* q_out, int kv_paged, void* kc,
+                               void* vc, const int32_t* page_table, int page_size, int max_pages,
+                               int64_t l_max, hipStream_t s) {
+  const dim3 grid(B, dm.Hq + 2 * dm.Hkv), block(dm.d / 2);
+  if (dm.dtype == 1)
+    hipLaunchKernelGGL(k_rope_kvwrite<bf16_t>, grid, block, 0, s, B, dm.Hq, dm.Hkv, dm.d, partial, nslices, planes,
+                       pos, dm.rope_theta, static_cast<bf16_t*>(q_out), kv_paged, static_cast<bf16_t*>(kc),
+                       static_cast<bf16_t*>(vc), page_table, page_size, max_pages, l_max);
+  else
+    hipLaunchKernelGGL(k_rope_kvwrite<float>, grid, block, 0, s, B, dm.Hq, dm.Hkv, dm.d, partial, nslices, planes,
+                       pos, dm.rope_theta, static_cast<float*>(q_out), kv_paged, static_cast<float*>(kc),
+                       static_cast<float*>(vc), page_table, page_size, max_pages, l_max);
+  return hipGetLastError();
+}
+
+hipError_t launch_silu_mul(const DraftDims& dm, int B, const float* partial, int nslices, int planes,
+                           float* act, uint4* apack, int pack_planes, hipStream_t s) {
+  const int MT = gemm_mt(B, pack_planes);
+  const int gy = (dm.I / 8 + 255) / 256;
+  hipLaunchKernelGGL(k_silu_mul, dim3(B, gy), dim3(256), 0, s, B, dm.I, partial, nslices, planes, act, apack, MT,
+                     pack_planes);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_finalize(const DraftDims& dm, int B, const int32_t* argmax_in, const float* extra,
+                                int32_t* next_tok, float* sig_raw, float* sig, hipStream_t s) {
+  hipLaunchKernelGGL(k_head_finalize, dim3(1), dim3(64), 0, s, B, dm.rem_activation, argmax_in, extra, next_tok,
+                     sig_raw, sig);
+  return hipGetLastError();
+}
+
+}  // namespace sx

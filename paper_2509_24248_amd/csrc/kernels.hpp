@@ -1,0 +1,118 @@
+// Internal launch interface between the C ABI layer and the HIP kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace sx {
+
+// out[m][n] = sum_k act[m][k] * w[n][k] for a weight matrix given as up to three
+// row blocks (q/k/v or gate/up share one launch).  Results are written as split-K
+// partial sums  partial[ks][v][n]  with v = m * planes + plane: consumers add the
+// ksplit * planes slices.  In head mode (V >= 0) rows n < V enter a fused argmax and
+// rows V.. are the signal rows of the widened head.
+struct GemmArgs {
+  const void* w[3];
+  int seg_end[3];      // exclusive end row of each block in the concatenated row space
+  int nseg;
+  int N, K, M;
+  int planes;          // MFMA path: 1 = activations exact in bf16, 2 = bf16 hi + lo parts
+  int ksplit;          // number of K ranges
+  int kb_per_split;    // MFMA path: 128-element K blocks per range
+  const float* act;    // VALU path: fp32 [M][K]
+  const uint4* apack;  // MFMA path: activation fragments, see pack_index()
+  float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
+  int V;               // head mode when >= 0
+  int n_extra;
+  float* part_val;     // head mode: [M][ntiles] best value per 16-row tile
+  int* part_idx;       //            [M][ntiles] its row index
+  float* extra_out;    // [M][n_extra] or nullptr
+  float* logits_dbg;   // [M][V] or nullptr
+};
+
+inline int gemm_ntiles(int N) { return (N + 15) / 16; }
+inline int gemm_mt(int M, int planes) { return (M * planes + 15) / 16; }
+
+// bytes of packed activation fragments for M rows of length K
+inline size_t apack_bytes(int M, int planes, int K) {
+  return static_cast<size_t>(K / 32) * gemm_mt(M, planes) * 64 * 16;
+}
+
+bool gemm_mfma_supported(int M, int planes, int K);
+void choose_ksplit(GemmArgs& g, bool mfma);
+hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s);
+hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
+// reduce per-tile partial argmaxes: one result per activation row
+hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, int ntiles, int M,
+                                  int32_t* argmax, float* max_logit, hipStream_t s);
+// VALU head path: logits [M][N] -> argmax over n < V, copy of signal rows and of logits
+hipError_t launch_argmax_rows(const float* logits, int M, int N, int V, int n_extra,
+                              int32_t* argmax, float* max_logit, float* extra_out,
+                              float* logits_dbg, hipStream_t s);
+// pack activations given in storage type (exact in bf16) into MFMA fragments
+hipError_t launch_pack_rows(const void* src, bool bf16, int M, int K, uint4* apack, float* act,
+                            hipStream_t s);
+
+// ---- attention -------------------------------------------------------------------------
+struct AttnArgs {
+  int dtype;                 // 0 fp32, 1 bf16
+  int paged;
+  const void *k, *v;
+  const int32_t* page_table;
+  int page_size, max_pages;
+  int64_t l_max;
+  int B, n_q, Hq, Hkv, d;
+  const void* q;             // [B, n_q, Hq, d]
+  const int32_t* ctx_len;    // [B] number of context entries before the block
+  const uint64_t* mask;      // [B, n_q] or nullptr = chain
+  float scale;
+  void* out;                 // [B, n_q, Hq, d] in dtype
+  int chunk;                 // keys per split
+  int nsplit;                // grid extent over splits
+  float* part_o;             // [B][Hkv][nsplit][R][d]
+  float* part_ml;            // [B][Hkv][nsplit][R][2]  (running max, sum)
+};
+void attn_plan(AttnArgs& a, int num_cus);
+size_t attn_workspace_bytes(const AttnArgs& a);
+hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
+
+// ---- draft-step glue kernels -----------------------------------------------------------
+struct DraftDims {
+  int dtype, D, Hq, Hkv, d, I, V;
+  float rms_eps, rope_theta;
+  int rem_activation;
+};
+hipError_t launch_embed_concat(const DraftDims& dm, int B, const void* embed, const int32_t* tok,
+                               const void* hidden_in, float* act, uint4* apack, hipStream_t s);
+// v[b][:] = residual[b][:] + sum of partial slices; optional copy to `sum_out` (fp32) and
+// `hidden_out` (storage type); then RMSNorm with gain -> act (fp32) and packed hi/lo fragments
+hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* partial, int nslices,
+                              int planes, const float* residual, const void* gain, float* sum_out,
+                              void* hidden_out, float* act, uint4* apack, int pack_planes,
+                              hipStream_t s);
+hipError_t launch_rope_kvwrite(const DraftDims& dm, int B, const float* partial, int nslices,
+                               int planes, const int32_t* pos, void* q_out, int kv_paged, void* kc,
+                               void* vc, const int32_t* page_table, int page_size, int max_pages,
+                               int64_t l_max, hipStream_t s);
+hipError_t launch_silu_mul(const DraftDims& dm, int B, const float* partial, int nslices, int planes,
+                           float* act, uint4* apack, int pack_planes, hipStream_t s);
+hipError_t launch_head_finalize(const DraftDims& dm, int B, const int32_t* argmax_in,
+                                const float* extra, int32_t* next_tok, float* sig_raw, float* sig,
+                                hipStream_t s);
+
+// ---- controller ------------------------------------------------------------------------
+struct ExitArgs {
+  float alpha, thr_conf, thr_prog, thr_rem;
+  uint32_t signal_mask;
+  int smoother, split_pick, check_root, stop_think_token;
+  int B, n_q, S;
+  const int32_t *block_tok, *parent, *target_argmax;
+  const float* sig;
+  const int32_t *ctx_len, *split_tok;
+  float* ewma;
+  int32_t *n_obs, *is_thinking;
+  int32_t *accept_len, *accept_path, *recover_tok, *last_node, *exit_flag, *new_ctx_len;
+};
+hipError_t launch_accept_exit(const ExitArgs& a, hipStream_t s);
+
+}  // namespace sx

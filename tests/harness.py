@@ -1,0 +1,185 @@
+"""Test-side plumbing: numpy inputs -> device tensors -> C-ABI calls -> numpy outputs.
+
+The same seeded arrays (workloads.gen) go to the oracle as float values and to
+the HIP library in the configuration's storage type."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import specexit_oracle as O
+from workloads import gen
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}      # max abs error relative to max(|ref|_inf, 1)
+
+
+def sx():
+    from paper_2509_24248_amd import binding
+    return binding
+
+
+def tdtype(shape):
+    return torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+
+
+def dev(x, shape=None, dtype=None):
+    """numpy -> cuda tensor; float arrays go to the storage type (values are representable)."""
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.uint64:
+        return torch.from_numpy(x.view(np.int64)).cuda()
+    t = torch.from_numpy(x).cuda()
+    if x.dtype.kind == "f":
+        t = t.to(dtype if dtype is not None else tdtype(shape))
+    return t.contiguous()
+
+
+def host(t):
+    return t.detach().float().cpu().numpy() if t.dtype in (torch.bfloat16, torch.float32) else t.cpu().numpy()
+
+
+def rel_err(got, ref):
+    ref = np.asarray(ref, dtype=np.float64)
+    return float(np.max(np.abs(np.asarray(got, dtype=np.float64) - ref)) / max(float(np.max(np.abs(ref))), 1.0))
+
+
+def workspace(nbytes):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+# ----------------------------------------------------------------------------- attention
+
+def kv_view_of(shape, kv: gen.KVCache):
+    lib = sx()
+    k, v = dev(kv.k, shape), dev(kv.v, shape)
+    pt = dev(kv.page_table) if kv.paged else None
+    return lib.kv_view(k, v, pt), (k, v, pt)
+
+
+def gpu_verify_attn(shape, kv, q, ctx_len, mask, scale=None):
+    lib = sx()
+    view, keep = kv_view_of(shape, kv)
+    B, n_q, Hq, d = q.shape
+    qd = dev(q, shape)
+    out = torch.empty_like(qd)
+    ws = workspace(lib.specexit_verify_attn_workspace_bytes(view, B, n_q, Hq))
+    lib.specexit_verify_attn(view, B, n_q, Hq, qd, dev(ctx_len.astype(np.int32)),
+                             None if mask is None else dev(mask), d ** -0.5 if scale is None else scale, out, ws)
+    torch.cuda.synchronize()
+    return host(out)
+
+
+def oracle_verify_attn(kv, q, ctx_len, mask, scale=None, only=None):
+    return O.verify_attn(q, kv.k, kv.v, ctx_len, mask, scale, kv.page_table if kv.paged else None, kv.page_size, only)
+
+
+# ----------------------------------------------------------------------------- LM head
+
+def force_gap(hidden, w, V, gap=0.05, shape=None, max_iter=20):
+    """Raise the winner's weight row until every hidden row has a top-2 logit gap > gap
+    (done with the oracle's logits; the bump keeps the storage type)."""
+    w = w.copy()
+    h64 = hidden.astype(np.float64)
+    for _ in range(max_iter):
+        am, z, _ = O.lmhead_argmax(hidden, w[:V])
+        g = O.top2_gap(z)
+        bad = np.flatnonzero(g < gap * 1.2)
+        if bad.size == 0:
+            return w, am, z
+        for r in bad:
+            bump = (gap * 2.0 - g[r]) * h64[r] / (h64[r] @ h64[r])
+            new = w[am[r]].astype(np.float64) + bump
+            w[am[r]] = gen.store(shape, new.astype(np.float32)) if shape is not None else new
+    raise AssertionError("could not force the logit gap")
+
+
+def gpu_lmhead(shape, hidden, w, n_extra=0, want_logits=True):
+    lib = sx()
+    M, D = hidden.shape
+    V = w.shape[0] - n_extra
+    dt = lib.BF16 if shape.dtype == "bf16" else lib.F32
+    hd, wd = dev(hidden, shape), dev(w, shape)
+    am = torch.empty(M, dtype=torch.int32, device="cuda")
+    mx = torch.empty(M, dtype=torch.float32, device="cuda")
+    ex = torch.empty((M, max(n_extra, 1)), dtype=torch.float32, device="cuda")
+    lg = torch.empty((M, V), dtype=torch.float32, device="cuda") if want_logits else None
+    ws = workspace(lib.specexit_lmhead_argmax_workspace_bytes(dt, M, D, V, n_extra))
+    lib.specexit_lmhead_argmax(dt, M, D, V, n_extra, hd, wd, am, mx, ex if n_extra else None, lg, ws)
+    torch.cuda.synchronize()
+    return host(am), host(mx), host(ex)[:, :n_extra], (host(lg) if want_logits else None)
+
+
+# ----------------------------------------------------------------------------- draft step
+
+class GpuDraft:
+    """Device-resident draft model + cache for repeated specexit_draft_step calls."""
+
+    def __init__(self, shape, w, kv: gen.KVCache, rem_activation=0):
+        lib = sx()
+        self.lib, self.shape = lib, shape
+        dt = lib.BF16 if shape.dtype == "bf16" else lib.F32
+        self.desc = lib.model_desc(dt, shape.D, shape.Hq, shape.Hkv, shape.d, shape.I, shape.V, shape.rms_eps,
+                                   shape.rope_theta, rem_activation)
+        self.wt = {n: dev(w[n], shape) for n in lib.WEIGHT_NAMES}
+        self.w = lib.draft_weights(self.wt)
+        self.view, self.keep = kv_view_of(shape, kv)
+        self.ws = workspace(lib.specexit_draft_step_workspace_bytes(self.desc, self.view, shape.B))
+        assert self.ws.numel() > 256, lib.last_error()
+
+    def step(self, tok, hidden_in, pos):
+        shape, B = self.shape, self.shape.B
+        hin = dev(hidden_in, shape)
+        hout = torch.empty_like(hin)
+        nt = torch.empty(B, dtype=torch.int32, device="cuda")
+        sr = torch.empty((B, 3), dtype=torch.float32, device="cuda")
+        sg = torch.empty((B, 3), dtype=torch.float32, device="cuda")
+        self.lib.specexit_draft_step(self.desc, self.w, self.view, B, dev(tok.astype(np.int32)), hin,
+                                     dev(pos.astype(np.int32)), hout, nt, sr, sg, self.ws)
+        torch.cuda.synchronize()
+        return {"hidden_out": host(hout), "next_tok": host(nt), "sig_raw": host(sr), "sig": host(sg)}
+
+    def cache(self):
+        return host(self.keep[0]), host(self.keep[1])
+
+
+def oracle_dims(shape):
+    return O.DraftDims(shape.D, shape.Hq, shape.Hkv, shape.d, shape.V, shape.rms_eps, shape.rope_theta)
+
+
+def force_draft_gap(shape, w, kv, tok, g, pos, gap=0.05):
+    """Run the oracle once to get the final-normed hidden rows, then bump w_head's winners."""
+    kc, vc = kv.k.astype(np.float64), kv.v.astype(np.float64)
+    out = O.draft_step(oracle_dims(shape), w, kc, vc, tok, g, pos, kv.page_table if kv.paged else None,
+                       kv.page_size, store=lambda a: gen.store(shape, a.astype(np.float32)))
+    head = w["w_head"]
+    V = shape.V
+    new_tok_rows, _, _ = force_gap(out["h_final"].astype(np.float32), head[:V], V, gap, shape)
+    w = dict(w)
+    w["w_head"] = np.concatenate([new_tok_rows, head[V:]], axis=0)
+    return w
+
+
+# ----------------------------------------------------------------------------- controller
+
+def gpu_accept_exit(cfg_kwargs, block_tok, parent, target_argmax, sig, ctx_len, split_tok, state):
+    """state = (ewma [B,3] f32, n_obs [B] i32, is_thinking [B] i32) device tensors, updated in place."""
+    lib = sx()
+    B, n_q = block_tok.shape
+    cfg = lib.exit_cfg(**cfg_kwargs)
+    i32 = lambda a: dev(np.asarray(a, dtype=np.int32))
+    outs = {k: torch.empty(B, dtype=torch.int32, device="cuda")
+            for k in ("accept_len", "recover_tok", "last_node", "exit_flag", "new_ctx_len")}
+    outs["accept_path"] = torch.empty((B, n_q), dtype=torch.int32, device="cuda")
+    split = i32(split_tok) if len(split_tok) else None
+    lib.specexit_accept_exit(cfg, B, n_q, i32(block_tok), None if parent is None else i32(parent),
+                             i32(target_argmax), dev(np.asarray(sig, np.float32), dtype=torch.float32),
+                             i32(ctx_len), split, len(split_tok), state[0], state[1], state[2],
+                             outs["accept_len"], outs["accept_path"], outs["recover_tok"], outs["last_node"],
+                             outs["exit_flag"], outs["new_ctx_len"])
+    torch.cuda.synchronize()
+    return {k: host(v) for k, v in outs.items()}
+
+
+def gpu_state(B):
+    return (torch.zeros((B, 3), dtype=torch.float32, device="cuda"),
+            torch.zeros(B, dtype=torch.int32, device="cuda"),
+            torch.ones(B, dtype=torch.int32, device="cuda"))

@@ -403,7 +403,7 @@ def accept_case(shape: Shape, seed: int = 0, parent: Optional[np.ndarray] = None
 def signal_series(shape: Shape, seed: int = 0, noise: float = 0.05):
     """[n_rounds, B, 3] fp32 raw (activated) signals per decode round.
 
-    Short series (<= 64 rounds): noisy monotone ramps.  Long series: per sequence
+    Short series (<= 64 rounds): noisy monotone ramps that level off after 60 % of the rounds.  Long series: per sequence
     a logistic ramp centred on a round tau_b ~ U{200..2000} (width 20 rounds),
     the long-reasoning regime.  Returns (series, tau) with tau None for ramps."""
     r = rng_for(shape, 12, seed)
@@ -411,7 +411,7 @@ def signal_series(shape: Shape, seed: int = 0, noise: float = 0.05):
     t = np.arange(T, dtype=np.float64)[:, None]
     eps = r.standard_normal((T, B, 3)) * noise
     if T <= 64:
-        f = t / T
+        f = np.minimum(1.0, t / (0.6 * T))      # ramp over the first 60 % of the rounds, then flat
         conf = np.clip(0.4 + 0.6 * f + eps[:, :, 0], 0.0, 1.0)
         prog = np.clip(f + eps[:, :, 1], 0.0, 1.0)
         rem = np.maximum(0.0, 2000.0 * (1.0 - f) * (1.0 + eps[:, :, 2]))
