@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of the SpecExit decode-round hot path on one MI355X.
+
+A "step" is one decode round: k x specexit_draft_step (chained), one
+specexit_verify_attn call (one target layer), one specexit_lmhead_argmax over the
+B*n_q block rows and one specexit_accept_exit.  Inputs are seeded synthetic tensors of
+the workload's shapes, resident in HBM before the timed region.  One JSON line is
+printed: rounds/s (value), draft tokens verified/s, the roofline of the dominant kernel
+(the widened-head weight-streaming GEMM of the draft step) measured live with HIP
+events, and the CPU oracle timed on the host cores as a baseline."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into the workload configurations (default: the metric's)")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    return ap.parse_args()
+
+
+class Round:
+    """Device-resident state of one decode round and the calls that run it."""
+
+    def __init__(self, shape, seed, keep_host=False):
+        import torch
+        from paper_2509_24248_amd import binding as sx
+        from workloads import gen
+        self.torch, self.sx, self.shape = torch, sx, shape
+        dt = torch.bfloat16 if shape.dtype == "bf16" else torch.float32
+        self.code = sx.BF16 if shape.dtype == "bf16" else sx.F32
+        B, n_q, k = shape.B, shape.n_q, shape.k
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        fdev = lambda a: dev(a).to(dt).contiguous()
+        host = {}
+        w = gen.draft_weights(shape, seed)
+        self.wt = {n: fdev(w[n]) for n in sx.WEIGHT_NAMES}
+        self.w = sx.draft_weights(self.wt)
+        lm = gen.lm_head(shape, seed)
+        self.lm = fdev(lm)
+        L = gen.context_lengths(shape, seed)
+        self.L = L
+        tkv = gen.kv_cache(shape, L, n_q, seed)                       # target layer cache, block K/V in place
+        dkv = gen.kv_cache(shape, L, k + 1, seed, stream=17)          # the draft layer's own cache
+        self.tk, self.tv = fdev(tkv.k), fdev(tkv.v)
+        self.dk, self.dv = fdev(dkv.k), fdev(dkv.v)
+        self.tpt = dev(tkv.page_table) if tkv.paged else None
+        self.dpt = dev(dkv.page_table) if dkv.paged else None
+        self.tview = sx.kv_view(self.tk, self.tv, self.tpt)
+        self.dview = sx.kv_view(self.dk, self.dv, self.dpt)
+        q = gen.queries(shape, seed)
+        self.q = fdev(q)
+        self.attn_out = torch.empty_like(self.q)
+        hid = gen.hidden_rows(shape, B * n_q, seed)
+        self.block_hidden = fdev(hid)                                   # target's final hidden rows of the block
+        g0 = gen.hidden_rows(shape, B, seed, stream=18)
+        self.g0 = fdev(g0)
+        tok0 = gen.token_ids(shape, B, seed)
+        self.tok0 = dev(tok0)
+        if shape.tree:
+            parent = gen.random_tree_parents(shape, seed)
+            mask = gen.ancestor_masks(parent)
+            self.parent = dev(parent)
+            self.mask = dev(mask.view(np.int64))
+            self.n_draft_steps = shape.k                                # one call per tree level
+        else:
+            self.parent, self.mask = None, None
+            self.n_draft_steps = shape.k
+        case = gen.accept_case(shape, seed, parent=parent if shape.tree else None)
+        self.block_tok = dev(case.block_tok)
+        self.split = dev(case.split_tok)
+        self.S = len(case.split_tok)
+        series, _ = gen.signal_series(shape, seed)
+        self.ctx = dev(L.astype(np.int32))
+        self.pos = [dev((L + j).astype(np.int32)) for j in range(self.n_draft_steps)]
+        i32 = lambda *s: torch.empty(s, dtype=torch.int32, device="cuda")
+        f32 = lambda *s: torch.empty(s, dtype=torch.float32, device="cuda")
+        self.hid = [torch.empty_like(self.g0) for _ in range(2)]
+        self.next_tok = [i32(B) for _ in range(self.n_draft_steps)]
+        self.sig_raw = [f32(B, 3) for _ in range(self.n_draft_steps)]
+        self.sig = [f32(B, 3) for _ in range(self.n_draft_steps)]
+        self.target_argmax = i32(B * n_q)
+        self.ewma = torch.zeros((B, 3), dtype=torch.float32, device="cuda")
+        self.n_obs = torch.zeros(B, dtype=torch.int32, device="cuda")
+        self.thinking = torch.ones(B, dtype=torch.int32, device="cuda")
+        self.accept_len, self.recover, self.last_node, self.exit_flag, self.new_ctx = (i32(B) for _ in range(5))
+        self.accept_path = i32(B, n_q)
+        self.desc = sx.model_desc(self.code, shape.D, shape.Hq, shape.Hkv, shape.d, shape.I, shape.V,
+                                  shape.rms_eps, shape.rope_theta, 0)
+        self.cfg = sx.exit_cfg(stop_think_token=case.stop_think_token)
+        ws = lambda n: torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
+        self.ws_draft = ws(sx.specexit_draft_step_workspace_bytes(self.desc, self.dview, B))
+        self.ws_attn = ws(sx.specexit_verify_attn_workspace_bytes(self.tview, B, n_q, shape.Hq))
+        self.ws_head = ws(sx.specexit_lmhead_argmax_workspace_bytes(self.code, B * n_q, shape.D, shape.V, 0))
+        self.scale = shape.d ** -0.5
+        if keep_host:
+            host.update(w=w, lm=lm, tkv=tkv, dkv=dkv, q=q, hid=hid, g0=g0, tok0=tok0, case=case, series=series,
+                        parent=parent if shape.tree else None, mask=mask if shape.tree else None)
+        self.host = host
+
+    def run(self):
+        sx, s = self.sx, self.shape
+        tok, hin = self.tok0, self.g0
+        for j in range(self.n_draft_steps):
+            hout = self.hid[j & 1]
+            sx.specexit_draft_step(self.desc, self.w, self.dview, s.B, tok, hin, self.pos[j], hout,
+                                   self.next_tok[j], self.sig_raw[j], self.sig[j], self.ws_draft)
+            tok, hin = self.next_tok[j], hout
+        sx.specexit_verify_attn(self.tview, s.B, s.n_q, s.Hq, self.q, self.ctx, self.mask, self.scale,
+                                self.attn_out, self.ws_attn)
+        sx.specexit_lmhead_argmax(self.code, s.B * s.n_q, s.D, s.V, 0, self.block_hidden, self.lm,
+                                  self.target_argmax, workspace=self.ws_head)
+        sx.specexit_accept_exit(self.cfg, s.B, s.n_q, self.block_tok, self.parent, self.target_argmax,
+                                self.sig[0], self.ctx, self.split, self.S, self.ewma, self.n_obs, self.thinking,
+                                self.accept_len, self.accept_path, self.recover, self.last_node, self.exit_flag,
+                                self.new_ctx)
+
+
+def cpu_baseline(rnd: Round):
+    """The oracle, as it stands, on the same inputs: one full round on the host cores."""
+    from oracle import specexit_oracle as O
+    from workloads import gen
+    s, h = rnd.shape, rnd.host
+    store = lambda a: gen.store(s, a.astype(np.float32))
+    dims = O.DraftDims(s.D, s.Hq, s.Hkv, s.d, s.V, s.rms_eps, s.rope_theta)
+    t0 = time.perf_counter()
+    kc, vc = h["dkv"].k.astype(np.float64), h["dkv"].v.astype(np.float64)
+    tok, g, sig0 = h["tok0"], h["g0"], None
+    for j in range(rnd.n_draft_steps):
+        out = O.draft_step(dims, h["w"], kc, vc, tok, g, rnd.L + j, h["dkv"].page_table if h["dkv"].paged else None,
+                           h["dkv"].page_size, store=store)
+        tok, g = out["next_tok"], store(out["hidden_out"])
+        sig0 = out["sig"] if sig0 is None else sig0
+    tk = h["tkv"]
+    O.verify_attn(h["q"], tk.k, tk.v, rnd.L, h["mask"], rnd.scale, tk.page_table if tk.paged else None, tk.page_size)
+    am, _, _ = O.lmhead_argmax(h["hid"], h["lm"])
+    c = h["case"]
+    O.accept_exit(O.ExitCfg(stop_think_token=c.stop_think_token), c.block_tok, h["parent"],
+                  am.reshape(s.B, s.n_q), sig0, rnd.L, c.split_tok, np.zeros((s.B, 3)), np.zeros(s.B, np.int32),
+                  np.ones(s.B, np.int32))
+    return time.perf_counter() - t0
+
+
+def threads_used():
+    try:
+        from threadpoolctl import threadpool_info
+        n = [p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"]
+        if n:
+            return int(max(n))
+    except Exception:
+        pass
+    return int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+
+
+def stored_traffic(shape_name):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_head_gemm_{shape_name}.json")
+    try:
+        with open(path) as fh:
+            return json.load(fh).get("bytes_per_launch")
+    except Exception:
+        return None
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one MI355X only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from workloads import gen
+    from paper_2509_24248_amd import binding as sx
+    assert torch.cuda.is_available(), "a GPU is required"
+    torch.cuda.set_device(0)
+    shape = gen.config(args.config)
+    want_cpu = not args.no_cpu_baseline and args.config <= 1
+    rnd = Round(shape, args.seed, keep_host=want_cpu)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(max(args.warmup, 1)):
+        rnd.run()
+    torch.cuda.synchronize()
+
+    # ---- eager leg with per-kernel events: duration of the dominant kernel, live
+    K = args.steps
+    n_ev = K * rnd.n_draft_steps
+    mk = lambda n: [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+    ev0, ev1 = mk(n_ev), mk(n_ev)
+    lm0, lm1 = mk(K), mk(K)
+    at0, at1 = mk(K), mk(K)
+    for e in ev0 + ev1 + lm0 + lm1 + at0 + at1:
+        e.record(stream)                                    # creates the underlying handles
+    torch.cuda.synchronize()
+    sx.specexit_profile_events(sx.PROF_DRAFT_HEAD_GEMM, ev0, ev1)
+    sx.specexit_profile_events(sx.PROF_LMHEAD_GEMM, lm0, lm1)
+    sx.specexit_profile_events(sx.PROF_VERIFY_ATTN, at0, at1)
+    e_start, e_stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e_start.record(stream)
+    for _ in range(K):
+        rnd.run()
+    e_stop.record(stream)
+    torch.cuda.synchronize()
+    eager_ms = e_start.elapsed_time(e_stop) / K
+    for kid in (sx.PROF_DRAFT_HEAD_GEMM, sx.PROF_LMHEAD_GEMM, sx.PROF_VERIFY_ATTN):
+        sx.specexit_profile_events(kid)
+    head_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev0, ev1)]))
+    lm_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(lm0, lm1)]))
+    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(at0, at1)]))
+
+    # ---- timed region for `value`: K rounds, replayed from a HIP graph unless --no-graph
+    graph_ms = None
+    if not args.no_graph:
+        try:
+            gstream = torch.cuda.Stream()
+            gstream.wait_stream(stream)
+            with torch.cuda.stream(gstream):
+                rnd.run()
+                torch.cuda.synchronize()
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=gstream):
+                    rnd.run()
+            torch.cuda.synchronize()
+            for _ in range(max(args.warmup, 1)):
+                graph.replay()
+            torch.cuda.synchronize()
+            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            g0.record(stream)
+            for _ in range(K):
+                graph.replay()
+            g1.record(stream)
+            torch.cuda.synchronize()
+            graph_ms = g0.elapsed_time(g1) / K
+        except Exception as exc:                                # report eager numbers if capture is refused
+            print(f"[bench] HIP graph capture unavailable ({exc}); reporting eager timing", file=sys.stderr)
+            graph_ms = None
+    ms = graph_ms if graph_ms is not None else eager_ms
+
+    e = 2 if shape.dtype == "bf16" else 4
+    head_bytes = e * (shape.V + 3) * shape.D + e * 2 * shape.B * shape.D + 8 * shape.B * ((shape.V + 18) // 16)
+    lm_bytes = e * shape.V * shape.D + e * shape.B * shape.n_q * shape.D
+    kv_bytes = 2 * e * shape.Hkv * shape.d * int((rnd.L + shape.n_q).sum()) + 2 * e * shape.B * shape.n_q * shape.Hq * shape.d
+    achieved = head_bytes / (head_ms * 1e-3) / 1e9
+    out = {
+        "metric": "verify rounds/sec (and draft tokens verified/sec) per MI355X",
+        "value": 1000.0 / ms,
+        "unit": "rounds/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": shape.dtype, "data": "synthetic",
+        "config": {"workload": f"configs[{shape.index}] {shape.name}: B={shape.B} chain k={shape.k} n_q={shape.n_q} "
+                               f"ctx={shape.ctx} D={shape.D} Hq/Hkv/d={shape.Hq}/{shape.Hkv}/{shape.d} V={shape.V} I={shape.I}; "
+                               "round = k draft steps + 1 target-layer verify attention + LM-head argmax + accept/exit",
+                   "launch": "hip-graph replay" if graph_ms is not None else "eager"},
+        "draft_tokens_verified_per_s": shape.B * (shape.n_q - 1) * 1000.0 / ms,
+        "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
+        "roofline": {"kernel": "k_gemm_mfma<1,2,true> (widened-head GEMM + argmax of the draft step)",
+                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(shape.name),
+                     "bytes_per_launch": head_bytes, "avg_launch_ms": head_ms},
+        "other_kernels": {
+            "lmhead_gemm": {"avg_launch_ms": lm_ms, "achieved_GBs": lm_bytes / (lm_ms * 1e-3) / 1e9, "bytes": lm_bytes},
+            "verify_attn_split": {"avg_launch_ms": attn_ms, "achieved_GBs": kv_bytes / (attn_ms * 1e-3) / 1e9, "bytes": kv_bytes}},
+    }
+    if want_cpu:
+        sec = cpu_baseline(rnd)
+        out["cpu_baseline"] = {"value": 1.0 / sec, "unit": "rounds/s", "cores": threads_used(), "kind": "oracle",
+                               "sample": f"one full round of the same workload and inputs ({sec:.1f} s of numpy float64)"}
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

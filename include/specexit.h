@@ -182,6 +182,19 @@ int32_t specexit_accept_exit(const specexit_exit_cfg *cfg, int32_t B, int32_t n_
                              int32_t *exit_flag /*[B]*/, int32_t *new_ctx_len /*[B]*/,
                              uint32_t flags, void *stream);
 
+/* ---- measurement aid -------------------------------------------------------------------
+ * Hands the library n pairs of caller-owned hipEvent_t ([host] arrays of handles).  From then
+ * on, each launch of the named kernel records the next unused pair around that one kernel on
+ * the call's stream (start before, stop after), until the pairs run out; n = 0 disarms.
+ * Returns the number of pairs consumed so far for that kernel when called with n < 0.
+ * Not thread-safe; do not arm while a stream is being captured into a graph. */
+#define SPECEXIT_PROF_DRAFT_HEAD_GEMM 0 /* widened-head GEMM + argmax inside specexit_draft_step */
+#define SPECEXIT_PROF_LMHEAD_GEMM     1 /* GEMM + argmax inside specexit_lmhead_argmax            */
+#define SPECEXIT_PROF_VERIFY_ATTN     2 /* split-KV kernel inside specexit_verify_attn            */
+#define SPECEXIT_PROF_DRAFT_ATTN      3 /* split-KV kernel inside specexit_draft_step             */
+int32_t specexit_profile_events(int32_t kernel, void *const *start_events, void *const *stop_events,
+                                int32_t n);
+
 const char *specexit_last_error(void); /* [host] thread-local, never NULL */
 uint32_t specexit_version(void);
 

@@ -24,8 +24,9 @@ EXPORTS = [
     "specexit_draft_step", "specexit_draft_step_workspace_bytes",
     "specexit_verify_attn", "specexit_verify_attn_workspace_bytes",
     "specexit_lmhead_argmax", "specexit_lmhead_argmax_workspace_bytes",
-    "specexit_accept_exit", "specexit_last_error", "specexit_version",
+    "specexit_accept_exit", "specexit_last_error", "specexit_version", "specexit_profile_events",
 ]
+PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
 
 
 class SpecExitError(RuntimeError):
@@ -87,6 +88,8 @@ def _load() -> C.CDLL:
     lib.specexit_accept_exit.restype = i32
     lib.specexit_accept_exit.argtypes = [C.POINTER(ExitCfg), i32, i32, vp, vp, vp, vp, vp, vp, i32,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+    lib.specexit_profile_events.restype = i32
+    lib.specexit_profile_events.argtypes = [i32, C.POINTER(vp), C.POINTER(vp), i32]
     return lib
 
 
@@ -221,3 +224,21 @@ def specexit_accept_exit(cfg: ExitCfg, B: int, n_q: int, block_tok, parent, targ
                                     _ptr(sig), _ptr(ctx_len), _ptr(split_tok), S, _ptr(ewma), _ptr(n_obs),
                                     _ptr(is_thinking), _ptr(accept_len), _ptr(accept_path), _ptr(recover_tok),
                                     _ptr(last_node), _ptr(exit_flag), _ptr(new_ctx_len), flags, _stream(stream)))
+
+
+def specexit_profile_events(kernel: int, start_events=None, stop_events=None) -> int:
+    """start_events/stop_events: lists of torch.cuda.Event(enable_timing=True) that have been
+    recorded once (so their handles exist); None disarms.  Returns the library's status."""
+    if not start_events:
+        return int(LIB.specexit_profile_events(kernel, None, None, 0))
+    n = len(start_events)
+    arr = C.c_void_p * n
+    a = arr(*[e.cuda_event for e in start_events])
+    b = arr(*[e.cuda_event for e in stop_events])
+    rc = LIB.specexit_profile_events(kernel, a, b, n)
+    _check(rc)
+    return rc
+
+
+def specexit_profile_events_used(kernel: int) -> int:
+    return int(LIB.specexit_profile_events(kernel, None, None, -1))

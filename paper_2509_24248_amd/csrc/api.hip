@@ -8,6 +8,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <vector>
+
 using namespace sx;
 
 namespace {
@@ -37,6 +39,39 @@ int num_cus() {
     if (n <= 0) n = 256;
   }
   return n;
+}
+
+// caller-provided event pairs recorded around single kernels (measurement aid)
+struct ProfSlot {
+  std::vector<hipEvent_t> start, stop;
+  size_t used = 0;
+};
+ProfSlot g_prof[4];
+
+struct ProfScope {
+  ProfSlot* slot;
+  hipStream_t s;
+  bool on;
+  ProfScope(int id, hipStream_t st) : slot(&g_prof[id]), s(st), on(slot->used < slot->start.size()) {
+    if (on) (void)hipEventRecord(slot->start[slot->used], s);
+  }
+  ~ProfScope() {
+    if (on) {
+      (void)hipEventRecord(slot->stop[slot->used], s);
+      ++slot->used;
+    }
+  }
+};
+
+void g_prof_hook(int id, int phase, hipStream_t s) {
+  ProfSlot& sl = g_prof[id];
+  if (sl.used >= sl.start.size()) return;
+  if (phase == 0) {
+    (void)hipEventRecord(sl.start[sl.used], s);
+  } else {
+    (void)hipEventRecord(sl.stop[sl.used], s);
+    ++sl.used;
+  }
 }
 
 size_t align256(size_t x) { return (x + 255) & ~static_cast<size_t>(255); }
@@ -225,6 +260,21 @@ int32_t run_gemm(GemmArgs g, bool mfma, bool bf16, const void* w0, const void* w
 extern "C" {
 
 const char* specexit_last_error(void) { return g_err; }
+
+int32_t specexit_profile_events(int32_t kernel, void* const* start_events, void* const* stop_events, int32_t n) {
+  if (kernel < 0 || kernel > 3) return fail(SPECEXIT_EINVAL, "profile_events: unknown kernel id %d", kernel);
+  ProfSlot& sl = g_prof[kernel];
+  if (n < 0) return static_cast<int32_t>(sl.used);
+  sl.start.clear();
+  sl.stop.clear();
+  sl.used = 0;
+  if (n > 0 && (!start_events || !stop_events)) return fail(SPECEXIT_EINVAL, "profile_events: event arrays are null");
+  for (int32_t i = 0; i < n; ++i) {
+    sl.start.push_back(static_cast<hipEvent_t>(start_events[i]));
+    sl.stop.push_back(static_cast<hipEvent_t>(stop_events[i]));
+  }
+  return SPECEXIT_OK;
+}
 uint32_t specexit_version(void) { return 0x00010000u; }
 
 size_t specexit_draft_step_workspace_bytes(const specexit_model_desc* desc, const specexit_kv_view* draft_kv, int32_t B) {
@@ -282,7 +332,7 @@ int32_t specexit_draft_step(const specexit_model_desc* desc, const specexit_draf
     at.part_o = c.take<float>(units * R * at.d * sizeof(float));
     at.part_ml = c.take<float>(units * R * 2 * sizeof(float));
   }
-  if ((rc = check_hip(launch_attn(at, s), "draft attention"))) return rc;
+  if ((rc = check_hip(launch_attn(at, s, &g_prof_hook, SPECEXIT_PROF_DRAFT_ATTN), "draft attention"))) return rc;
   // a = x + W_o attn
   if ((rc = check_hip(launch_pack_rows(b.attn_out, bf16, B, dm.Hq * dm.d, ap, b.act, s), "pack attn"))) return rc;
   if ((rc = run_gemm(p.o, mf, bf16, w->w_o, nullptr, nullptr, b, s, "gemm o"))) return rc;
@@ -295,7 +345,10 @@ int32_t specexit_draft_step(const specexit_model_desc* desc, const specexit_draf
   if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.down.ksplit, p.down.planes, b.a_buf, w->ln_final,
                                          nullptr, hidden_out, b.act, ap, pp, s), "norm final"))) return rc;
   // widened head (Eq. 1): argmax over the vocabulary rows, three signal rows on the side
-  if ((rc = run_gemm(p.head, mf, bf16, w->w_head, nullptr, nullptr, b, s, "gemm head"))) return rc;
+  {
+    ProfScope prof(SPECEXIT_PROF_DRAFT_HEAD_GEMM, s);
+    if ((rc = run_gemm(p.head, mf, bf16, w->w_head, nullptr, nullptr, b, s, "gemm head"))) return rc;
+  }
   if (mf) {
     if ((rc = check_hip(launch_argmax_finalize(b.part_val, b.part_idx, p.ntiles_head, B, b.head_am, nullptr, s), "argmax finalize"))) return rc;
   } else {
@@ -332,7 +385,7 @@ int32_t specexit_verify_attn(const specexit_kv_view* kv, int32_t B, int32_t n_q,
   const size_t units = static_cast<size_t>(a.B) * a.Hkv * a.nsplit;
   a.part_o = c.take<float>(units * R * a.d * sizeof(float));
   a.part_ml = c.take<float>(units * R * 2 * sizeof(float));
-  return check_hip(launch_attn(a, static_cast<hipStream_t>(stream)), "verify_attn");
+  return check_hip(launch_attn(a, static_cast<hipStream_t>(stream), &g_prof_hook, SPECEXIT_PROF_VERIFY_ATTN), "verify_attn");
 }
 
 namespace {
@@ -395,7 +448,10 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
     g.apack = ap;
     g.part_val = pv;
     g.part_idx = pi;
-    if ((rc = check_hip(launch_gemm_mfma(g, s), "gemm lm head"))) return rc;
+    {
+      ProfScope prof(SPECEXIT_PROF_LMHEAD_GEMM, s);
+      if ((rc = check_hip(launch_gemm_mfma(g, s), "gemm lm head"))) return rc;
+    }
     return check_hip(launch_argmax_finalize(pv, pi, h.ntiles, M, argmax, max_logit, s), "argmax finalize");
   }
   if (bf16) {
@@ -405,7 +461,10 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
     g.act = static_cast<const float*>(hidden);
   }
   g.partial = partial;
-  if ((rc = check_hip(launch_gemm_valu(g, bf16, s), "gemv lm head"))) return rc;
+  {
+    ProfScope prof(SPECEXIT_PROF_LMHEAD_GEMM, s);
+    if ((rc = check_hip(launch_gemm_valu(g, bf16, s), "gemv lm head"))) return rc;
+  }
   return check_hip(launch_argmax_rows(partial, M, V + n_extra, V, n_extra, argmax, max_logit,
                                       n_extra ? extra_out : nullptr, logits_dbg, s), "argmax rows");
 }

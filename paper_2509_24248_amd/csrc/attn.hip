@@ -236,13 +236,15 @@ size_t attn_workspace_bytes(const AttnArgs& a) {
   return o + ml;
 }
 
-hipError_t launch_attn(const AttnArgs& a, hipStream_t s) {
+hipError_t launch_attn(const AttnArgs& a, hipStream_t s, KernelHook hook, int hook_id) {
   hipError_t e;
+  if (hook) hook(hook_id, 0, s);
   if (a.dtype == 1) {
     e = a.d == 128 ? launch_valu<bf16_t, 128>(a, s) : launch_valu<bf16_t, 64>(a, s);
   } else {
     e = a.d == 128 ? launch_valu<float, 128>(a, s) : launch_valu<float, 64>(a, s);
   }
+  if (hook) hook(hook_id, 1, s);
   if (e != hipSuccess) return e;
   if (a.dtype == 1)
     hipLaunchKernelGGL(k_attn_combine<bf16_t>, dim3(a.Hq, a.n_q, a.B), dim3(a.d), 0, s, a);

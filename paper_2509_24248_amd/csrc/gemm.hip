@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void k_gemv_valu(const GemmArgs g) {
 }
 
 // ------------------------------------------------------------------------- MFMA path
-template <int MT, int PLANES>
+template <int MT, int PLANES, bool HEAD>
 __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmArgs g) {
   // one 16-row x 128-k weight tile (4 KB) per wave; entry [row][pos] holds the 16-byte
   // chunk (pos ^ row) of that row, so both the coalesced writes and the per-row operand
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmArgs g) {
   // accumulator layout: lane (c = lane % 16, q = lane / 16) holds rows n0 + 4q + i of
   // activation column 16 t + c
   const int Mv = g.M * PLANES;
-  if (g.V < 0) {
+  if (!HEAD) {
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
       const int v = 16 * t + fr;
@@ -333,28 +333,29 @@ hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int PLANES>
+template <int PLANES, bool HEAD>
 static hipError_t launch_mfma_planes(const GemmArgs& g, hipStream_t s) {
   const int mt = gemm_mt(g.M, PLANES);
   const dim3 grid((gemm_ntiles(g.N) + 3) / 4, g.ksplit);
   const dim3 block(256);
   switch (mt) {
-    case 1: hipLaunchKernelGGL((k_gemm_mfma<1, PLANES>), grid, block, 0, s, g); break;
-    case 2: hipLaunchKernelGGL((k_gemm_mfma<2, PLANES>), grid, block, 0, s, g); break;
-    case 3: hipLaunchKernelGGL((k_gemm_mfma<3, PLANES>), grid, block, 0, s, g); break;
-    case 4: hipLaunchKernelGGL((k_gemm_mfma<4, PLANES>), grid, block, 0, s, g); break;
-    case 5: hipLaunchKernelGGL((k_gemm_mfma<5, PLANES>), grid, block, 0, s, g); break;
-    case 6: hipLaunchKernelGGL((k_gemm_mfma<6, PLANES>), grid, block, 0, s, g); break;
-    case 7: hipLaunchKernelGGL((k_gemm_mfma<7, PLANES>), grid, block, 0, s, g); break;
-    case 8: hipLaunchKernelGGL((k_gemm_mfma<8, PLANES>), grid, block, 0, s, g); break;
-    case 9: hipLaunchKernelGGL((k_gemm_mfma<9, PLANES>), grid, block, 0, s, g); break;
+    case 1: hipLaunchKernelGGL((k_gemm_mfma<1, PLANES, HEAD>), grid, block, 0, s, g); break;
+    case 2: hipLaunchKernelGGL((k_gemm_mfma<2, PLANES, HEAD>), grid, block, 0, s, g); break;
+    case 3: hipLaunchKernelGGL((k_gemm_mfma<3, PLANES, HEAD>), grid, block, 0, s, g); break;
+    case 4: hipLaunchKernelGGL((k_gemm_mfma<4, PLANES, HEAD>), grid, block, 0, s, g); break;
+    case 5: hipLaunchKernelGGL((k_gemm_mfma<5, PLANES, HEAD>), grid, block, 0, s, g); break;
+    case 6: hipLaunchKernelGGL((k_gemm_mfma<6, PLANES, HEAD>), grid, block, 0, s, g); break;
+    case 7: hipLaunchKernelGGL((k_gemm_mfma<7, PLANES, HEAD>), grid, block, 0, s, g); break;
+    case 8: hipLaunchKernelGGL((k_gemm_mfma<8, PLANES, HEAD>), grid, block, 0, s, g); break;
+    case 9: hipLaunchKernelGGL((k_gemm_mfma<9, PLANES, HEAD>), grid, block, 0, s, g); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
-  return g.planes == 2 ? launch_mfma_planes<2>(g, s) : launch_mfma_planes<1>(g, s);
+  if (g.V >= 0) return g.planes == 2 ? launch_mfma_planes<2, true>(g, s) : launch_mfma_planes<1, true>(g, s);
+  return g.planes == 2 ? launch_mfma_planes<2, false>(g, s) : launch_mfma_planes<1, false>(g, s);
 }
 
 hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, int ntiles, int M,

@@ -74,7 +74,9 @@ struct AttnArgs {
 };
 void attn_plan(AttnArgs& a, int num_cus);
 size_t attn_workspace_bytes(const AttnArgs& a);
-hipError_t launch_attn(const AttnArgs& a, hipStream_t s);
+// hook(id, 0 / 1, stream) is called right before / after the split-KV kernel's launch
+typedef void (*KernelHook)(int id, int phase, hipStream_t s);
+hipError_t launch_attn(const AttnArgs& a, hipStream_t s, KernelHook hook = nullptr, int hook_id = 0);
 
 // ---- draft-step glue kernels -----------------------------------------------------------
 struct DraftDims {
