@@ -211,7 +211,6 @@ int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specex
 
 struct DraftBufs {
   float* act;
-  uint4* apack;
   float* partial;
   float *x_buf, *a_buf;
   void *q_buf, *attn_out;
@@ -228,7 +227,6 @@ DraftBufs carve_draft(const DraftPlan& p, void* ws) {
   DraftBufs b;
   const size_t es = esize(p.dm.dtype);
   b.act = c.take<float>(sizeof(float) * p.B * p.Kmax);
-  b.apack = c.take<uint4>(apack_bytes(p.B, 2, (p.Kmax + 127) / 128 * 128));
   b.partial = c.take<float>(p.partial_bytes);
   b.x_buf = c.take<float>(sizeof(float) * p.B * p.dm.D);
   b.a_buf = c.take<float>(sizeof(float) * p.B * p.dm.D);
@@ -247,7 +245,7 @@ int32_t run_gemm(GemmArgs g, bool mfma, bool bf16, const void* w0, const void* w
                  const DraftBufs& b, hipStream_t s, const char* what) {
   g.w[0] = w0; g.w[1] = w1; g.w[2] = w2;
   g.act = b.act;
-  g.apack = b.apack;
+  if (g.a_mode == 0) g.a_src = b.act;
   g.partial = b.partial;
   g.part_val = b.part_val;
   g.part_idx = b.part_idx;
@@ -306,14 +304,19 @@ int32_t specexit_draft_step(const specexit_model_desc* desc, const specexit_draf
   const DraftDims& dm = p.dm;
   const bool bf16 = dm.dtype == SPECEXIT_BF16;
   const bool mf = p.mfma;
-  uint4* ap = mf ? b.apack : nullptr;
-  const int pp = mf ? 2 : 1;
 
   // x = W_fc [embed[tok] ; hidden_in]
-  if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, tok, hidden_in, b.act, ap, s), "embed_concat"))) return rc;
+  if (mf) {
+    p.fc.a_mode = 2;   // the GEMM gathers [embed[tok] ; hidden_in] itself
+    p.fc.a_src = hidden_in;
+    p.fc.a_embed = w->embed;
+    p.fc.a_tok = tok;
+  } else {
+    if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, tok, hidden_in, b.act, s), "embed_concat"))) return rc;
+  }
   if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
   if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.fc.ksplit, p.fc.planes, nullptr, w->ln_attn,
-                                         b.x_buf, nullptr, b.act, ap, pp, s), "norm attn"))) return rc;
+                                         b.x_buf, nullptr, b.act, s), "norm attn"))) return rc;
   // q, k, v; rotary; cache write; attention over the draft's own cache
   if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
   if ((rc = check_hip(launch_rope_kvwrite(dm, B, b.partial, p.qkv.ksplit, p.qkv.planes, pos, b.q_buf, p.attn.paged,
@@ -334,16 +337,21 @@ int32_t specexit_draft_step(const specexit_model_desc* desc, const specexit_draf
   }
   if ((rc = check_hip(launch_attn(at, s, &g_prof_hook, SPECEXIT_PROF_DRAFT_ATTN), "draft attention"))) return rc;
   // a = x + W_o attn
-  if ((rc = check_hip(launch_pack_rows(b.attn_out, bf16, B, dm.Hq * dm.d, ap, b.act, s), "pack attn"))) return rc;
+  if (mf) {
+    p.o.a_mode = 1;    // attention output is read in its storage type
+    p.o.a_src = b.attn_out;
+  } else {
+    if ((rc = check_hip(launch_unpack_rows(b.attn_out, bf16, B, dm.Hq * dm.d, b.act, s), "unpack attn"))) return rc;
+  }
   if ((rc = run_gemm(p.o, mf, bf16, w->w_o, nullptr, nullptr, b, s, "gemm o"))) return rc;
   if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.o.ksplit, p.o.planes, b.x_buf, w->ln_mlp,
-                                         b.a_buf, nullptr, b.act, ap, pp, s), "norm mlp"))) return rc;
+                                         b.a_buf, nullptr, b.act, s), "norm mlp"))) return rc;
   // y = a + W_down (silu(W_gate m) * W_up m)
   if ((rc = run_gemm(p.gu, mf, bf16, w->w_gate, w->w_up, nullptr, b, s, "gemm gate/up"))) return rc;
-  if ((rc = check_hip(launch_silu_mul(dm, B, b.partial, p.gu.ksplit, p.gu.planes, b.act, ap, pp, s), "silu"))) return rc;
+  if ((rc = check_hip(launch_silu_mul(dm, B, b.partial, p.gu.ksplit, p.gu.planes, b.act, s), "silu"))) return rc;
   if ((rc = run_gemm(p.down, mf, bf16, w->w_down, nullptr, nullptr, b, s, "gemm down"))) return rc;
   if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.down.ksplit, p.down.planes, b.a_buf, w->ln_final,
-                                         nullptr, hidden_out, b.act, ap, pp, s), "norm final"))) return rc;
+                                         nullptr, hidden_out, b.act, s), "norm final"))) return rc;
   // widened head (Eq. 1): argmax over the vocabulary rows, three signal rows on the side
   {
     ProfScope prof(SPECEXIT_PROF_DRAFT_HEAD_GEMM, s);
@@ -393,7 +401,7 @@ struct HeadPlan {
   bool mfma;
   GemmArgs g;
   int ntiles;
-  size_t act_bytes, apack_bytes_, partial_bytes, pv_bytes;
+  size_t act_bytes, partial_bytes, pv_bytes;
 };
 int32_t make_head_plan(HeadPlan& h, int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra) {
   if (!dtype_ok(dtype)) return fail(SPECEXIT_EINVAL, "lmhead_argmax: unknown dtype %d", dtype);
@@ -405,7 +413,6 @@ int32_t make_head_plan(HeadPlan& h, int32_t dtype, int32_t M, int32_t D, int32_t
   h.g.n_extra = n_extra;
   h.ntiles = gemm_ntiles(V + n_extra);
   h.act_bytes = (!h.mfma && dtype == SPECEXIT_BF16) ? sizeof(float) * M * D : 0;
-  h.apack_bytes_ = h.mfma ? apack_bytes(M, 1, D) : 0;
   h.partial_bytes = h.mfma ? 0 : sizeof(float) * M * (static_cast<size_t>(V) + n_extra);
   h.pv_bytes = h.mfma ? sizeof(float) * M * h.ntiles : 0;
   return SPECEXIT_OK;
@@ -415,7 +422,7 @@ int32_t make_head_plan(HeadPlan& h, int32_t dtype, int32_t M, int32_t D, int32_t
 size_t specexit_lmhead_argmax_workspace_bytes(int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra) {
   HeadPlan h;
   if (make_head_plan(h, dtype, M, D, V, n_extra)) return 0;
-  size_t t = align256(h.act_bytes) + align256(h.apack_bytes_) + align256(h.partial_bytes) + 2 * align256(h.pv_bytes);
+  size_t t = align256(h.act_bytes) + align256(h.partial_bytes) + 2 * align256(h.pv_bytes);
   return t ? t : 256;
 }
 
@@ -434,7 +441,6 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
   hipStream_t s = static_cast<hipStream_t>(stream);
   Carver c(workspace);
   float* act = c.take<float>(h.act_bytes);
-  uint4* ap = c.take<uint4>(h.apack_bytes_);
   float* partial = c.take<float>(h.partial_bytes);
   float* pv = c.take<float>(h.pv_bytes);
   int* pi = c.take<int>(h.pv_bytes);
@@ -444,8 +450,8 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
   g.logits_dbg = logits_dbg;
   const bool bf16 = dtype == SPECEXIT_BF16;
   if (h.mfma) {
-    if ((rc = check_hip(launch_pack_rows(hidden, true, M, D, ap, nullptr, s), "pack hidden"))) return rc;
-    g.apack = ap;
+    g.a_mode = 1;
+    g.a_src = hidden;
     g.part_val = pv;
     g.part_idx = pi;
     {
@@ -455,7 +461,7 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
     return check_hip(launch_argmax_finalize(pv, pi, h.ntiles, M, argmax, max_logit, s), "argmax finalize");
   }
   if (bf16) {
-    if ((rc = check_hip(launch_pack_rows(hidden, true, M, D, nullptr, act, s), "unpack hidden"))) return rc;
+    if ((rc = check_hip(launch_unpack_rows(hidden, true, M, D, act, s), "unpack hidden"))) return rc;
     g.act = act;
   } else {
     g.act = static_cast<const float*>(hidden);

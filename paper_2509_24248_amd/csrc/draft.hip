@@ -1,8 +1,7 @@
 // Row-wise glue of the draft step (Sec. 3.1; Alg. 1 first loop line): everything between
 // the weight-streaming GEMMs.  Each kernel reduces the split-K partial sums of the GEMM
 // before it, applies the layer's elementwise math in fp32 and emits the next GEMM's
-// activations, both as an fp32 row (ALU GEMM path) and as packed bf16 MFMA fragments
-// (hi part, optionally plus the bf16 rounding remainder so fp32 activations lose nothing).
+// activations as fp32 rows (the MFMA GEMM splits them into bf16 hi + lo parts itself).
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -19,27 +18,6 @@ __device__ __forceinline__ float block_sum_256(float v, float* sh) {
   const float r = sh[0] + sh[1] + sh[2] + sh[3];
   __syncthreads();
   return r;
-}
-
-// write 8 consecutive activations of row m starting at k = 8 * g8 into the fragments
-__device__ __forceinline__ void pack_store(uint4* apack, int MT, int planes, int m, int g8,
-                                           const float (&f)[8]) {
-  const int s = g8 >> 2, q = g8 & 3;
-  uint32_t hi[4], lo[4];
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const bf16_t h0 = f32_to_bf16(f[2 * e]), h1 = f32_to_bf16(f[2 * e + 1]);
-    hi[e] = static_cast<uint32_t>(h0) | (static_cast<uint32_t>(h1) << 16);
-    const bf16_t l0 = f32_to_bf16(f[2 * e] - bf16_to_f32(h0));
-    const bf16_t l1 = f32_to_bf16(f[2 * e + 1] - bf16_to_f32(h1));
-    lo[e] = static_cast<uint32_t>(l0) | (static_cast<uint32_t>(l1) << 16);
-  }
-  const int v = m * planes;
-  apack[(static_cast<size_t>(s) * MT + (v >> 4)) * 64 + (v & 15) + 16 * q] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-  if (planes == 2) {
-    const int v1 = v + 1;
-    apack[(static_cast<size_t>(s) * MT + (v1 >> 4)) * 64 + (v1 & 15) + 16 * q] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-  }
 }
 
 // sum over split-K ranges and planes of 8 consecutive outputs of row b
@@ -63,8 +41,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void k_embed_concat(int D, const T* __restrict__ embed,
                                                       const int32_t* __restrict__ tok,
                                                       const T* __restrict__ hidden_in,
-                                                      float* __restrict__ act, uint4* __restrict__ apack,
-                                                      int MT) {
+                                                      float* __restrict__ act) {
   const int b = blockIdx.x;
   const T* e = embed + static_cast<size_t>(tok[b]) * D;
   const T* h = hidden_in + static_cast<size_t>(b) * D;
@@ -76,7 +53,6 @@ __global__ __launch_bounds__(256) void k_embed_concat(int D, const T* __restrict
     for (int i = 0; i < 8; ++i) f[i] = Elem<T>::load(src + i);
 #pragma unroll
     for (int i = 0; i < 8; ++i) act[static_cast<size_t>(b) * 2 * D + k + i] = f[i];
-    if (apack) pack_store(apack, MT, 1, b, g8, f);
   }
 }
 
@@ -86,8 +62,7 @@ __global__ __launch_bounds__(256) void k_reduce_norm(int B, int N, const float* 
                                                      const float* __restrict__ residual,
                                                      const T* __restrict__ gain, float eps,
                                                      float* __restrict__ sum_out, T* __restrict__ hidden_out,
-                                                     float* __restrict__ act, uint4* __restrict__ apack,
-                                                     int MT, int pack_planes) {
+                                                     float* __restrict__ act) {
   __shared__ float sh[4];
   const int b = blockIdx.x;
   float vals[kMaxGroups][8];
@@ -122,7 +97,6 @@ __global__ __launch_bounds__(256) void k_reduce_norm(int B, int N, const float* 
       for (int e = 0; e < 8; ++e) f[e] = vals[it][e] * rinv * Elem<T>::load(gain + g8 * 8 + e);
 #pragma unroll
       for (int e = 0; e < 8; ++e) act[static_cast<size_t>(b) * N + g8 * 8 + e] = f[e];
-      if (apack) pack_store(apack, MT, pack_planes, b, g8, f);
     }
   }
 }
@@ -177,8 +151,7 @@ __global__ void k_rope_kvwrite(int B, int Hq, int Hkv, int d, const float* __res
 }
 
 __global__ __launch_bounds__(256) void k_silu_mul(int B, int I, const float* __restrict__ partial,
-                                                  int nslices, int planes, float* __restrict__ act,
-                                                  uint4* __restrict__ apack, int MT, int pack_planes) {
+                                                  int nslices, int planes, float* __restrict__ act) {
   const int b = blockIdx.x;
   for (int g8 = blockIdx.y * 256 + threadIdx.x; g8 < I / 8; g8 += 256 * gridDim.y) {
     float gt[8], up[8], f[8];
@@ -188,7 +161,6 @@ __global__ __launch_bounds__(256) void k_silu_mul(int B, int I, const float* __r
     for (int e = 0; e < 8; ++e) f[e] = gt[e] * sigmoidf_(gt[e]) * up[e];
 #pragma unroll
     for (int e = 0; e < 8; ++e) act[static_cast<size_t>(b) * I + g8 * 8 + e] = f[e];
-    if (apack) pack_store(apack, MT, pack_planes, b, g8, f);
   }
 }
 
@@ -219,30 +191,25 @@ __global__ void k_head_finalize(int B, int rem_activation, const int32_t* __rest
 }  // namespace
 
 hipError_t launch_embed_concat(const DraftDims& dm, int B, const void* embed, const int32_t* tok,
-                               const void* hidden_in, float* act, uint4* apack, hipStream_t s) {
-  const int MT = gemm_mt(B, 1);
+                               const void* hidden_in, float* act, hipStream_t s) {
   if (dm.dtype == 1)
     hipLaunchKernelGGL(k_embed_concat<bf16_t>, dim3(B), dim3(256), 0, s, dm.D, static_cast<const bf16_t*>(embed),
-                       tok, static_cast<const bf16_t*>(hidden_in), act, apack, MT);
+                       tok, static_cast<const bf16_t*>(hidden_in), act);
   else
     hipLaunchKernelGGL(k_embed_concat<float>, dim3(B), dim3(256), 0, s, dm.D, static_cast<const float*>(embed),
-                       tok, static_cast<const float*>(hidden_in), act, apack, MT);
+                       tok, static_cast<const float*>(hidden_in), act);
   return hipGetLastError();
 }
 
 hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* partial, int nslices,
                               int planes, const float* residual, const void* gain, float* sum_out,
-                              void* hidden_out, float* act, uint4* apack, int pack_planes,
-                              hipStream_t s) {
-  const int MT = gemm_mt(B, pack_planes);
+                              void* hidden_out, float* act, hipStream_t s) {
   if (dm.dtype == 1)
     hipLaunchKernelGGL(k_reduce_norm<bf16_t>, dim3(B), dim3(256), 0, s, B, N, partial, nslices, planes, residual,
-                       static_cast<const bf16_t*>(gain), dm.rms_eps, sum_out, static_cast<bf16_t*>(hidden_out), act,
-                       apack, MT, pack_planes);
+                       static_cast<const bf16_t*>(gain), dm.rms_eps, sum_out, static_cast<bf16_t*>(hidden_out), act);
   else
     hipLaunchKernelGGL(k_reduce_norm<float>, dim3(B), dim3(256), 0, s, B, N, partial, nslices, planes, residual,
-                       static_cast<const float*>(gain), dm.rms_eps, sum_out, static_cast<float*>(hidden_out), act,
-                       apack, MT, pack_planes);
+                       static_cast<const float*>(gain), dm.rms_eps, sum_out, static_cast<float*>(hidden_out), act);
   return hipGetLastError();
 }
 
@@ -263,11 +230,9 @@ hipError_t launch_rope_kvwrite(const DraftDims& dm, int B, const float* partial,
 }
 
 hipError_t launch_silu_mul(const DraftDims& dm, int B, const float* partial, int nslices, int planes,
-                           float* act, uint4* apack, int pack_planes, hipStream_t s) {
-  const int MT = gemm_mt(B, pack_planes);
+                           float* act, hipStream_t s) {
   const int gy = (dm.I / 8 + 255) / 256;
-  hipLaunchKernelGGL(k_silu_mul, dim3(B, gy), dim3(256), 0, s, B, dm.I, partial, nslices, planes, act, apack, MT,
-                     pack_planes);
+  hipLaunchKernelGGL(k_silu_mul, dim3(B, gy), dim3(256), 0, s, B, dm.I, partial, nslices, planes, act);
   return hipGetLastError();
 }
 

@@ -91,22 +91,76 @@ __global__ __launch_bounds__(256) void k_gemv_valu(const GemmArgs g) {
 }
 
 // ------------------------------------------------------------------------- MFMA path
+constexpr int kGemmWaves = 8;   // waves per workgroup, one 16-row weight tile each
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// The weight stream is read exactly once: non-temporal loads keep it from displacing the
+// small, reused operands in L2 and measurably raise the achieved HBM rate.
+__device__ __forceinline__ uint4 load_stream16(const char* p) {
+  const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  return static_cast<uint32_t>(f32_to_bf16(a)) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
+}
+
+// Stage the activations of K elements [k0, k0 + kc) in LDS as MFMA operand pieces:
+// entry ((s * 4 + q) * Mv + v) holds virtual row v's 8 values k0 + 32 s + 8 q .. + 7 as
+// bf16.  Virtual row v = m * PLANES + plane: plane 0 is the bf16 rounding of the value,
+// plane 1 the bf16 rounding of what that lost (fp32 activations keep ~16 mantissa bits).
+template <int PLANES>
+__device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_lds, int k0, int kc, int nthreads) {
+  const int Mv = g.M * PLANES;
+  const int groups = kc >> 3;
+  for (int idx = threadIdx.x; idx < g.M * groups; idx += nthreads) {
+    const int m = idx / groups, g8 = idx - m * groups;
+    const int k = k0 + g8 * 8;
+    uint4 hi, lo = make_uint4(0, 0, 0, 0);
+    if (g.a_mode == 0) {
+      const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(g.a_src) + static_cast<size_t>(m) * g.K + k);
+      const float4 x = src[0], y = src[1];
+      hi = make_uint4(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w), pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w));
+      if (PLANES == 2) {
+        float f[8];
+        unpack16(hi, f);
+        lo = make_uint4(pack_bf16x2(x.x - f[0], x.y - f[1]), pack_bf16x2(x.z - f[2], x.w - f[3]),
+                        pack_bf16x2(y.x - f[4], y.y - f[5]), pack_bf16x2(y.z - f[6], y.w - f[7]));
+      }
+    } else if (g.a_mode == 1) {
+      hi = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.a_src) + static_cast<size_t>(m) * g.K + k);
+    } else {
+      const int half = g.K >> 1;
+      const bf16_t* src = k < half ? static_cast<const bf16_t*>(g.a_embed) + static_cast<size_t>(g.a_tok[m]) * half + k
+                                   : static_cast<const bf16_t*>(g.a_src) + static_cast<size_t>(m) * half + (k - half);
+      hi = *reinterpret_cast<const uint4*>(src);
+    }
+    const int s = g8 >> 2, q = g8 & 3;
+    a_lds[(s * 4 + q) * Mv + m * PLANES] = hi;
+    if (PLANES == 2) a_lds[(s * 4 + q) * Mv + m * PLANES + 1] = lo;
+  }
+}
+
 template <int MT, int PLANES, bool HEAD>
-__global__ __launch_bounds__(256) void k_gemm_mfma(const GemmArgs g) {
-  // one 16-row x 128-k weight tile (4 KB) per wave; entry [row][pos] holds the 16-byte
-  // chunk (pos ^ row) of that row, so both the coalesced writes and the per-row operand
-  // reads touch 16 distinct 16-byte slots
-  __shared__ uint4 lds[4][256];
+__global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g) {
+  // LDS: [activation pieces of one K chunk][per wave: one 16-row x 128-k weight tile, 4 KB]
+  // weight tile entry [row][pos] holds the 16-byte piece (pos ^ row) of that row, so both the
+  // coalesced writes and the per-row operand reads touch 16 distinct 16-byte slots
+  extern __shared__ uint4 dyn_lds[];
+  const int Mv = g.M * PLANES;
+  uint4* a_lds = dyn_lds;
+  uint4* w_lds = dyn_lds + (g.kc >> 3) * Mv;
   const int lane = threadIdx.x & 63;
   const int wv = threadIdx.x >> 6;
   const int ntiles = (g.N + 15) >> 4;
-  const int tile = blockIdx.x * 4 + wv;
-  if (tile >= ntiles) return;  // waves are independent: no block-level barrier below
+  const int tile = blockIdx.x * kGemmWaves + wv;
+  const bool active = tile < ntiles;   // idle waves still take part in the barriers
   const int ks = blockIdx.y;
   const int KB = g.K >> 7;
   const int kb0 = ks * g.kb_per_split;
   const int kb1 = min(KB, kb0 + g.kb_per_split);
-  const int n0 = tile << 4;
+  const int n0 = (active ? tile : ntiles - 1) << 4;
   const SegRef sg = find_segment(g, n0);
   const size_t row_bytes = static_cast<size_t>(g.K) * 2;
 
@@ -119,43 +173,51 @@ __global__ __launch_bounds__(256) void k_gemm_mfma(const GemmArgs g) {
     src[i] = sg.base + static_cast<size_t>(lr) * row_bytes + static_cast<size_t>((pos ^ r) << 4);
   }
   const int fr = lane & 15, fq = lane >> 4;
-  uint4* my = lds[wv];
+  uint4* my = w_lds + wv * 256;
 
   f32x4_t acc[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  const uint4* ap = g.apack + (static_cast<size_t>(kb0) * 4 * MT) * 64 + lane;
-  for (int kb = kb0; kb < kb1; ++kb) {
-    uint4 wr[4];
+  const int kcb = g.kc >> 7;           // 128-element blocks per staged chunk
+  for (int c0 = kb0; c0 < kb1; c0 += kcb) {
+    const int c1 = min(kb1, c0 + kcb);
+    if (c0 != kb0) __syncthreads();    // everyone is done with the previous chunk
+    stage_activations<PLANES>(g, a_lds, c0 << 7, (c1 - c0) << 7, 64 * kGemmWaves);
+    __syncthreads();
+    if (!active) continue;
+    for (int kb = c0; kb < c1; ++kb) {
+      uint4 wr[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      wr[i] = *reinterpret_cast<const uint4*>(src[i] + (static_cast<size_t>(kb) << 8));
+      for (int i = 0; i < 4; ++i) wr[i] = load_stream16(src[i] + (static_cast<size_t>(kb) << 8));
 #pragma unroll
-    for (int i = 0; i < 4; ++i) my[(4 * i + (lane >> 4)) * 16 + pos] = wr[i];
-    // the tile is private to this wave, whose LDS operations retire in order: a compiler
-    // fence is all that separates the writes from the transposed reads
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      for (int i = 0; i < 4; ++i) my[(4 * i + (lane >> 4)) * 16 + pos] = wr[i];
+      // the tile is private to this wave, whose LDS operations retire in order: a compiler
+      // fence is all that separates the writes from the transposed reads
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const uint4* ab = a_lds + ((kb - c0) * 16 + fq) * Mv;
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const uint4 wf = my[fr * 16 + ((4 * s + fq) ^ fr)];
-      const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, wf);
+      for (int s = 0; s < 4; ++s) {
+        const uint4 wf = my[fr * 16 + ((4 * s + fq) ^ fr)];
+        const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, wf);
 #pragma unroll
-      for (int t = 0; t < MT; ++t) {
-        const uint4 af = ap[(s * MT + t) * 64];
-        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8_t, af), acc[t], 0, 0, 0);
+        for (int t = 0; t < MT; ++t) {
+          const int v = 16 * t + fr;
+          uint4 af = ab[s * 4 * Mv + (v < Mv ? v : 0)];
+          if (v >= Mv) af = make_uint4(0, 0, 0, 0);
+          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8_t, af), acc[t], 0, 0, 0);
+        }
       }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
-    ap += 4 * MT * 64;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
   }
+  if (!active) return;
 
   // accumulator layout: lane (c = lane % 16, q = lane / 16) holds rows n0 + 4q + i of
   // activation column 16 t + c
-  const int Mv = g.M * PLANES;
   if (!HEAD) {
 #pragma unroll
     for (int t = 0; t < MT; ++t) {
@@ -275,30 +337,11 @@ __global__ __launch_bounds__(256) void k_argmax_rows(const float* __restrict__ l
   }
 }
 
-// Fragment layout of packed activations: for k-step s (32 values of k), column block t,
-// lane (c, q) = (lane % 16, lane / 16) holds act[16 t + c][32 s + 8 q .. + 7] as bf16.
 template <typename T>
-__global__ __launch_bounds__(256) void k_pack_rows(const T* __restrict__ src, int M, int K, int MT,
-                                                   uint4* __restrict__ apack, float* __restrict__ act) {
+__global__ __launch_bounds__(256) void k_unpack_rows(const T* __restrict__ src, int K, float* __restrict__ act) {
   const int m = blockIdx.x;
-  const T* row = src + static_cast<size_t>(m) * K;
-  for (int g8 = threadIdx.x; g8 < K / 8; g8 += 256) {
-    float f[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) f[e] = Elem<T>::load(row + g8 * 8 + e);
-    if (act) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) act[static_cast<size_t>(m) * K + g8 * 8 + e] = f[e];
-    }
-    if (apack) {
-      uint32_t p[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        p[e] = static_cast<uint32_t>(f32_to_bf16(f[2 * e])) | (static_cast<uint32_t>(f32_to_bf16(f[2 * e + 1])) << 16);
-      const int s = g8 >> 2, q = g8 & 3;
-      apack[(static_cast<size_t>(s) * MT + (m >> 4)) * 64 + (m & 15) + 16 * q] = make_uint4(p[0], p[1], p[2], p[3]);
-    }
-  }
+  for (int k = threadIdx.x; k < K; k += 256)
+    act[static_cast<size_t>(m) * K + k] = Elem<T>::load(src + static_cast<size_t>(m) * K + k);
 }
 
 }  // namespace
@@ -309,19 +352,32 @@ bool gemm_mfma_supported(int M, int planes, int K) {
 }
 
 void choose_ksplit(GemmArgs& g, bool mfma) {
-  if (!mfma || g.V >= 0) {
+  const int KB = g.K / 128;
+  if (!mfma) {
     g.ksplit = 1;
-    g.kb_per_split = g.K / 128;
+    g.kb_per_split = KB;
+    g.kc = g.K;
     return;
   }
-  const int KB = g.K / 128;
-  const int ntiles = gemm_ntiles(g.N);
-  int want = (4096 + ntiles - 1) / ntiles;
-  if (want < 1) want = 1;
-  if (want > KB) want = KB;
-  if (want > 32) want = 32;
-  g.kb_per_split = (KB + want - 1) / want;
-  g.ksplit = (KB + g.kb_per_split - 1) / g.kb_per_split;
+  if (g.V >= 0) {
+    g.ksplit = 1;
+    g.kb_per_split = KB;
+  } else {
+    // enough (tile, K range) units to give every SIMD a few waves
+    const int ntiles = gemm_ntiles(g.N);
+    int want = (2048 + ntiles - 1) / ntiles;
+    if (want < 1) want = 1;
+    if (want > KB) want = KB;
+    if (want > 16) want = 16;
+    g.kb_per_split = (KB + want - 1) / want;
+    g.ksplit = (KB + g.kb_per_split - 1) / g.kb_per_split;
+  }
+  // activations staged in LDS per chunk: whole K range if it fits in 64 KB
+  const int Mv = g.M * g.planes;
+  int kcb = (64 * 1024) / (Mv * 128 * 2);
+  if (kcb < 1) kcb = 1;
+  if (kcb > g.kb_per_split) kcb = g.kb_per_split;
+  g.kc = kcb * 128;
 }
 
 hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
@@ -333,24 +389,38 @@ hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
   return hipGetLastError();
 }
 
+size_t gemm_mfma_lds_bytes(const GemmArgs& g) {
+  return (static_cast<size_t>(g.kc >> 3) * g.M * g.planes + static_cast<size_t>(kGemmWaves) * 256) * 16;
+}
+
+template <int MT, int PLANES, bool HEAD>
+static hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
+  static bool attr_set = false;
+  if (!attr_set) {
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_mfma<MT, PLANES, HEAD>),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const dim3 grid((gemm_ntiles(g.N) + kGemmWaves - 1) / kGemmWaves, g.ksplit);
+  hipLaunchKernelGGL((k_gemm_mfma<MT, PLANES, HEAD>), grid, dim3(64 * kGemmWaves), gemm_mfma_lds_bytes(g), s, g);
+  return hipGetLastError();
+}
+
 template <int PLANES, bool HEAD>
 static hipError_t launch_mfma_planes(const GemmArgs& g, hipStream_t s) {
-  const int mt = gemm_mt(g.M, PLANES);
-  const dim3 grid((gemm_ntiles(g.N) + 3) / 4, g.ksplit);
-  const dim3 block(256);
-  switch (mt) {
-    case 1: hipLaunchKernelGGL((k_gemm_mfma<1, PLANES, HEAD>), grid, block, 0, s, g); break;
-    case 2: hipLaunchKernelGGL((k_gemm_mfma<2, PLANES, HEAD>), grid, block, 0, s, g); break;
-    case 3: hipLaunchKernelGGL((k_gemm_mfma<3, PLANES, HEAD>), grid, block, 0, s, g); break;
-    case 4: hipLaunchKernelGGL((k_gemm_mfma<4, PLANES, HEAD>), grid, block, 0, s, g); break;
-    case 5: hipLaunchKernelGGL((k_gemm_mfma<5, PLANES, HEAD>), grid, block, 0, s, g); break;
-    case 6: hipLaunchKernelGGL((k_gemm_mfma<6, PLANES, HEAD>), grid, block, 0, s, g); break;
-    case 7: hipLaunchKernelGGL((k_gemm_mfma<7, PLANES, HEAD>), grid, block, 0, s, g); break;
-    case 8: hipLaunchKernelGGL((k_gemm_mfma<8, PLANES, HEAD>), grid, block, 0, s, g); break;
-    case 9: hipLaunchKernelGGL((k_gemm_mfma<9, PLANES, HEAD>), grid, block, 0, s, g); break;
+  switch (gemm_mt(g.M, PLANES)) {
+    case 1: return launch_one<1, PLANES, HEAD>(g, s);
+    case 2: return launch_one<2, PLANES, HEAD>(g, s);
+    case 3: return launch_one<3, PLANES, HEAD>(g, s);
+    case 4: return launch_one<4, PLANES, HEAD>(g, s);
+    case 5: return launch_one<5, PLANES, HEAD>(g, s);
+    case 6: return launch_one<6, PLANES, HEAD>(g, s);
+    case 7: return launch_one<7, PLANES, HEAD>(g, s);
+    case 8: return launch_one<8, PLANES, HEAD>(g, s);
+    case 9: return launch_one<9, PLANES, HEAD>(g, s);
     default: return hipErrorInvalidValue;
   }
-  return hipGetLastError();
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
@@ -371,13 +441,11 @@ hipError_t launch_argmax_rows(const float* logits, int M, int N, int V, int n_ex
   return hipGetLastError();
 }
 
-hipError_t launch_pack_rows(const void* src, bool bf16, int M, int K, uint4* apack, float* act,
-                            hipStream_t s) {
-  const int MT = gemm_mt(M, 1);
+hipError_t launch_unpack_rows(const void* src, bool bf16, int M, int K, float* act, hipStream_t s) {
   if (bf16)
-    hipLaunchKernelGGL(k_pack_rows<bf16_t>, dim3(M), dim3(256), 0, s, static_cast<const bf16_t*>(src), M, K, MT, apack, act);
+    hipLaunchKernelGGL(k_unpack_rows<bf16_t>, dim3(M), dim3(256), 0, s, static_cast<const bf16_t*>(src), K, act);
   else
-    hipLaunchKernelGGL(k_pack_rows<float>, dim3(M), dim3(256), 0, s, static_cast<const float*>(src), M, K, MT, apack, act);
+    hipLaunchKernelGGL(k_unpack_rows<float>, dim3(M), dim3(256), 0, s, static_cast<const float*>(src), K, act);
   return hipGetLastError();
 }
 

@@ -20,7 +20,13 @@ struct GemmArgs {
   int ksplit;          // number of K ranges
   int kb_per_split;    // MFMA path: 128-element K blocks per range
   const float* act;    // VALU path: fp32 [M][K]
-  const uint4* apack;  // MFMA path: activation fragments, see pack_index()
+  // MFMA path: where the activations come from
+  int a_mode;          // 0: fp32 rows [M][K]; 1: bf16 rows [M][K];
+                       // 2: bf16 [embed[tok[m]] ; hidden[m]], each K/2 wide (the draft's fuse input)
+  const void* a_src;   // rows (modes 0, 1) or hidden rows (mode 2)
+  const void* a_embed; // mode 2: embedding table [V][K/2]
+  const int32_t* a_tok;  // mode 2: token ids [M]
+  int kc;              // K elements of activations staged in LDS at a time (multiple of 128)
   float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
   int V;               // head mode when >= 0
   int n_extra;
@@ -33,11 +39,6 @@ struct GemmArgs {
 inline int gemm_ntiles(int N) { return (N + 15) / 16; }
 inline int gemm_mt(int M, int planes) { return (M * planes + 15) / 16; }
 
-// bytes of packed activation fragments for M rows of length K
-inline size_t apack_bytes(int M, int planes, int K) {
-  return static_cast<size_t>(K / 32) * gemm_mt(M, planes) * 64 * 16;
-}
-
 bool gemm_mfma_supported(int M, int planes, int K);
 void choose_ksplit(GemmArgs& g, bool mfma);
 hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s);
@@ -49,9 +50,8 @@ hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, in
 hipError_t launch_argmax_rows(const float* logits, int M, int N, int V, int n_extra,
                               int32_t* argmax, float* max_logit, float* extra_out,
                               float* logits_dbg, hipStream_t s);
-// pack activations given in storage type (exact in bf16) into MFMA fragments
-hipError_t launch_pack_rows(const void* src, bool bf16, int M, int K, uint4* apack, float* act,
-                            hipStream_t s);
+// storage-type rows -> fp32 rows (ALU GEMM path only)
+hipError_t launch_unpack_rows(const void* src, bool bf16, int M, int K, float* act, hipStream_t s);
 
 // ---- attention -------------------------------------------------------------------------
 struct AttnArgs {
@@ -85,19 +85,18 @@ struct DraftDims {
   int rem_activation;
 };
 hipError_t launch_embed_concat(const DraftDims& dm, int B, const void* embed, const int32_t* tok,
-                               const void* hidden_in, float* act, uint4* apack, hipStream_t s);
+                               const void* hidden_in, float* act, hipStream_t s);
 // v[b][:] = residual[b][:] + sum of partial slices; optional copy to `sum_out` (fp32) and
-// `hidden_out` (storage type); then RMSNorm with gain -> act (fp32) and packed hi/lo fragments
+// `hidden_out` (storage type); then RMSNorm with gain -> act (fp32)
 hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* partial, int nslices,
                               int planes, const float* residual, const void* gain, float* sum_out,
-                              void* hidden_out, float* act, uint4* apack, int pack_planes,
-                              hipStream_t s);
+                              void* hidden_out, float* act, hipStream_t s);
 hipError_t launch_rope_kvwrite(const DraftDims& dm, int B, const float* partial, int nslices,
                                int planes, const int32_t* pos, void* q_out, int kv_paged, void* kc,
                                void* vc, const int32_t* page_table, int page_size, int max_pages,
                                int64_t l_max, hipStream_t s);
 hipError_t launch_silu_mul(const DraftDims& dm, int B, const float* partial, int nslices, int planes,
-                           float* act, uint4* apack, int pack_planes, hipStream_t s);
+                           float* act, hipStream_t s);
 hipError_t launch_head_finalize(const DraftDims& dm, int B, const int32_t* argmax_in,
                                 const float* extra, int32_t* next_tok, float* sig_raw, float* sig,
                                 hipStream_t s);
