@@ -143,6 +143,7 @@ def draft_weights(tensors: dict) -> DraftWeights:
         t = tensors[n]
         assert t.is_cuda and t.is_contiguous()
         setattr(w, n, t.data_ptr())
+    w._keep = [tensors[n] for n in WEIGHT_NAMES]
     return w
 
 
@@ -167,6 +168,7 @@ def kv_view(k: torch.Tensor, v: torch.Tensor, page_table: Optional[torch.Tensor]
         kv.page_table = page_table.data_ptr()
         kv.page_size, kv.max_pages_per_seq = k.shape[2], page_table.shape[1]
         kv.l_max, kv.n_pages = page_table.shape[1] * k.shape[2], k.shape[0]
+    kv._keep = (k, v, page_table)      # the view holds raw addresses: keep their tensors alive with it
     return kv
 
 

@@ -184,7 +184,7 @@ __global__ void k_attn_combine(const AttnArgs a) {
   for (int s = 0; s < nact; ++s) {
     const float ms = a.part_ml[((unit0 + s) * R + r) * 2];
     if (ms == -INFINITY) continue;
-    const float w = expf(ms - mmax);
+    const float w = a.use_mfma ? exp2f(ms - mmax) : expf(ms - mmax);
     den = fmaf(w, a.part_ml[((unit0 + s) * R + r) * 2 + 1], den);
     num = fmaf(w, a.part_o[((unit0 + s) * R + r) * a.d + c], num);
   }
@@ -218,7 +218,9 @@ void attn_plan(AttnArgs& a, int num_cus) {
   // chip about twice when every sequence is at its longest, never below 128 keys
   const int64_t units = static_cast<int64_t>(a.B) * a.Hkv;
   const int64_t lmax = a.l_max;
-  int64_t chunk = (units * lmax + 2 * num_cus - 1) / (2 * num_cus);
+  a.use_mfma = attn_mfma_supported(a) ? 1 : 0;
+  const int64_t target = (a.use_mfma ? 3 : 2) * static_cast<int64_t>(num_cus);
+  int64_t chunk = (units * lmax + target - 1) / target;
   chunk = ((chunk + 127) / 128) * 128;
   if (chunk < 128) chunk = 128;
   a.chunk = static_cast<int>(chunk);
@@ -239,7 +241,9 @@ size_t attn_workspace_bytes(const AttnArgs& a) {
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s, KernelHook hook, int hook_id) {
   hipError_t e;
   if (hook) hook(hook_id, 0, s);
-  if (a.dtype == 1) {
+  if (a.use_mfma) {
+    e = launch_attn_mfma(a, s);
+  } else if (a.dtype == 1) {
     e = a.d == 128 ? launch_valu<bf16_t, 128>(a, s) : launch_valu<bf16_t, 64>(a, s);
   } else {
     e = a.d == 128 ? launch_valu<float, 128>(a, s) : launch_valu<float, 64>(a, s);

@@ -71,7 +71,10 @@ struct AttnArgs {
   int nsplit;                // grid extent over splits
   float* part_o;             // [B][Hkv][nsplit][R][d]
   float* part_ml;            // [B][Hkv][nsplit][R][2]  (running max, sum)
+  int use_mfma;              // matrix-core kernel (bf16, head_dim 128); its maxima are in log2 units
 };
+bool attn_mfma_supported(const AttnArgs& a);
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 void attn_plan(AttnArgs& a, int num_cus);
 size_t attn_workspace_bytes(const AttnArgs& a);
 // hook(id, 0 / 1, stream) is called right before / after the split-KV kernel's launch
