@@ -33,10 +33,6 @@ __device__ __forceinline__ uint4 ld_stream16(const char* p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-__device__ __forceinline__ uint32_t bf16_pair(float a, float b) {
-  return static_cast<uint32_t>(f32_to_bf16(a)) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
-}
-
 // key handled by load instruction i (0..7) of lane group u = lane / 16: consecutive
 // instructions of a lane fetch keys 2m and 2m+1, which sit next to each other in a V^T row
 __device__ __forceinline__ int tile_key(int i, int u) { return 2 * (4 * (i >> 1) + u) + (i & 1); }
@@ -49,7 +45,7 @@ __device__ __forceinline__ int vt_pos(int key) { return ((key & 12) << 1) | ((ke
 // (R <= 64).  NG = 2: two row groups of up to 64 rows; the two waves of a group split the
 // key tiles two ways (each tile is then fetched by one wave of either group: the second
 // fetch is served by the cache, HBM still sees it once).
-template <int RT, int NG>
+template <int RT, int NG, bool PAGED>
 __global__ __launch_bounds__(64 * kAW) void k_attn_mfma(const AttnArgs a) {
   constexpr int KW = kAW / NG;          // waves sharing a row group = ways the keys are split
   extern __shared__ uint4 smem4[];
@@ -97,30 +93,60 @@ __global__ __launch_bounds__(64 * kAW) void k_attn_mfma(const AttnArgs a) {
   }
   const float sl2 = a.scale * 1.44269504088896340736f;  // scores are kept in log2 units
 
+  // Addresses: a 64-bit base per (sequence, head) or per page, plus 32-bit offsets.  A tile is
+  // 32 keys starting at a multiple of 32, so with pages of 16 * 2^n tokens it touches at most
+  // two pages: the one of key 0 and the one of key 16.  Their ids are fetched one tile ahead
+  // of the K/V loads that need them, so no load ever waits on a page-table read.
   const int ps_shift = 31 - __builtin_clz(a.page_size);
-  auto row_ptr = [&](const void* pool, int p) -> const char* {
-    size_t row;
-    if (a.paged) {
-      const int page = a.page_table[static_cast<size_t>(b) * a.max_pages + (p >> ps_shift)];
-      row = (static_cast<size_t>(page) * a.Hkv + g) * a.page_size + (p & (a.page_size - 1));
-    } else {
-      row = (static_cast<size_t>(b) * a.Hkv + g) * a.l_max + p;
+  const char* kbase = static_cast<const char*>(a.k);
+  const char* vbase = static_cast<const char*>(a.v);
+  const uint32_t lane_off = (lane & 15) << 4;
+  size_t seq_row = 0;
+  const int32_t* ptab = nullptr;
+  if (PAGED) {
+    ptab = a.page_table + static_cast<size_t>(b) * a.max_pages;
+  } else {
+    seq_row = (static_cast<size_t>(b) * a.Hkv + g) * a.l_max;
+  }
+  int pg_a = 0, pg_b = 0;   // page ids of the tile whose K/V are fetched next
+  auto fetch_pages = [&](int t0) {
+    if (PAGED) {
+      pg_a = ptab[t0 >> ps_shift];
+      pg_b = ptab[min(t0 + 16, s1 - 1) >> ps_shift];
     }
-    return static_cast<const char*>(pool) + row * 256 + ((lane & 15) << 4);
   };
 
   uint4 kreg[8], vreg[8];
   auto fetch = [&](int t0) {
+    size_t row_a, row_b = 0;
+    if (PAGED) {
+      row_a = (static_cast<size_t>(pg_a) * a.Hkv + g) * a.page_size;
+      row_b = (static_cast<size_t>(pg_b) * a.Hkv + g) * a.page_size;
+    } else {
+      row_a = seq_row + t0;
+    }
+    const int page0 = t0 >> ps_shift;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int p = min(t0 + tile_key(i, fq), s1 - 1);  // keys past the range are masked below
-      kreg[i] = ld_stream16(row_ptr(a.k, p));
-      vreg[i] = ld_stream16(row_ptr(a.v, p));
+      size_t off;
+      if (PAGED) {
+        const size_t row = ((p >> ps_shift) == page0 ? row_a : row_b) + (p & (a.page_size - 1));
+        off = row * 256 + lane_off;
+      } else {
+        off = (row_a + static_cast<uint32_t>(p - t0)) * 256 + lane_off;
+      }
+      kreg[i] = ld_stream16(kbase + off);
+      vreg[i] = ld_stream16(vbase + off);
     }
   };
 
   int t0 = s0 + 32 * kw;
-  if (t0 < s1) fetch(t0);
+  if (t0 < s1) {
+    fetch_pages(t0);
+    fetch(t0);
+    if (t0 + 32 * KW < s1) fetch_pages(t0 + 32 * KW);
+  }
   for (; t0 < s1; t0 += 32 * KW) {
     // ---- registers -> LDS: K swizzled rows, V transposed
 #pragma unroll
@@ -141,7 +167,10 @@ __global__ __launch_bounds__(64 * kAW) void k_attn_mfma(const AttnArgs a) {
       }
     }
     const int tnext = t0 + 32 * KW;
-    if (tnext < s1) fetch(tnext);
+    if (tnext < s1) {
+      fetch(tnext);                                         // page ids arrived during the last tile
+      if (tnext + 32 * KW < s1) fetch_pages(tnext + 32 * KW);
+    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -198,11 +227,8 @@ __global__ __launch_bounds__(64 * kAW) void k_attn_mfma(const AttnArgs a) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) pr[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
       }
-      pf[t] = make_uint4(bf16_pair(pr[0], pr[1]), bf16_pair(pr[2], pr[3]), bf16_pair(pr[4], pr[5]), bf16_pair(pr[6], pr[7]));
-      // the row sum uses the same rounded probabilities that multiply V
-      float f[8];
-      unpack16(pf[t], f);
-      l_run[t] = l_run[t] * al + (((f[0] + f[1]) + (f[2] + f[3])) + ((f[4] + f[5]) + (f[6] + f[7])));
+      pf[t] = make_uint4(pack_bf16x2(pr[0], pr[1]), pack_bf16x2(pr[2], pr[3]), pack_bf16x2(pr[4], pr[5]), pack_bf16x2(pr[6], pr[7]));
+      l_run[t] = l_run[t] * al + (((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7])));
       m_run[t] = m_new;
       alpha[t] = al;
       rescale = rescale || (al != 1.f);
@@ -300,17 +326,22 @@ size_t mfma_smem_bytes(int RT, int NG) {
   return tiles + static_cast<size_t>(kAW) * 16 * RT * 2 * sizeof(float);
 }
 
-template <int RT, int NG>
-hipError_t launch_rt(const AttnArgs& a, hipStream_t s) {
+template <int RT, int NG, bool PAGED>
+hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_mfma<RT, NG>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_mfma<RT, NG, PAGED>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_attn_mfma<RT, NG>), dim3(a.nsplit, a.Hkv, a.B), dim3(64 * kAW), mfma_smem_bytes(RT, NG), s, a);
+  hipLaunchKernelGGL((k_attn_mfma<RT, NG, PAGED>), dim3(a.nsplit, a.Hkv, a.B), dim3(64 * kAW), mfma_smem_bytes(RT, NG), s, a);
   return hipGetLastError();
+}
+
+template <int RT, int NG>
+hipError_t launch_rt(const AttnArgs& a, hipStream_t s) {
+  return a.paged ? launch_one<RT, NG, true>(a, s) : launch_one<RT, NG, false>(a, s);
 }
 
 }  // namespace
@@ -318,7 +349,7 @@ hipError_t launch_rt(const AttnArgs& a, hipStream_t s) {
 bool attn_mfma_supported(const AttnArgs& a) {
   const int R = (a.Hq / a.Hkv) * a.n_q;
   const bool pow2 = (a.page_size & (a.page_size - 1)) == 0;
-  return a.dtype == 1 && a.d == 128 && R <= 128 && (!a.paged || pow2);
+  return a.dtype == 1 && a.d == 128 && R <= 128 && (!a.paged || (pow2 && a.page_size >= 16));
 }
 
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {

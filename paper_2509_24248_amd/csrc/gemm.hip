@@ -102,10 +102,6 @@ __device__ __forceinline__ uint4 load_stream16(const char* p) {
   return make_uint4(t.x, t.y, t.z, t.w);
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
-  return static_cast<uint32_t>(f32_to_bf16(a)) | (static_cast<uint32_t>(f32_to_bf16(b)) << 16);
-}
-
 // Stage the activations of K elements [k0, k0 + kc) in LDS as MFMA operand pieces:
 // entry ((s * 4 + q) * Mv + v) holds virtual row v's 8 values k0 + 32 s + 8 q .. + 7 as
 // bf16.  Virtual row v = m * PLANES + plane: plane 0 is the bf16 rounding of the value,
