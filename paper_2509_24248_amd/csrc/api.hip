@@ -357,11 +357,10 @@ int32_t specexit_draft_step(const specexit_model_desc* desc, const specexit_draf
     ProfScope prof(SPECEXIT_PROF_DRAFT_HEAD_GEMM, s);
     if ((rc = run_gemm(p.head, mf, bf16, w->w_head, nullptr, nullptr, b, s, "gemm head"))) return rc;
   }
-  if (mf) {
-    if ((rc = check_hip(launch_argmax_finalize(b.part_val, b.part_idx, p.ntiles_head, B, b.head_am, nullptr, s), "argmax finalize"))) return rc;
-  } else {
-    if ((rc = check_hip(launch_argmax_rows(b.partial, B, dm.V + 3, dm.V, 3, b.head_am, nullptr, b.extra, nullptr, s), "argmax rows"))) return rc;
-  }
+  if (mf)
+    return check_hip(launch_argmax_finalize(b.part_val, b.part_idx, p.ntiles_head, B, next_tok, nullptr, s, b.extra,
+                                            dm.rem_activation, sig_raw, sig), "argmax finalize");
+  if ((rc = check_hip(launch_argmax_rows(b.partial, B, dm.V + 3, dm.V, 3, b.head_am, nullptr, b.extra, nullptr, s), "argmax rows"))) return rc;
   return check_hip(launch_head_finalize(dm, B, b.head_am, b.extra, next_tok, sig_raw, sig, s), "head finalize");
 }
 

@@ -167,29 +167,55 @@ __global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
   }
 }
 
-// Merge the chunks of one (sequence, query, head): exact log-sum-exp combination.
-template <typename T>
-__global__ void k_attn_combine(const AttnArgs a) {
+// Merge the chunks of one (sequence, query, head): exact log-sum-exp combination.  One wave
+// per output row; the chunk maxima are scanned lane-parallel, the partial outputs are
+// accumulated four chunks at a time so that their loads overlap.
+template <typename T, int D>
+__global__ __launch_bounds__(64) void k_attn_combine(const AttnArgs a) {
+  constexpr int PER = D / 64;   // output columns per lane
   const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
-  const int c = threadIdx.x;  // < d
+  const int lane = threadIdx.x;
   const int G = a.Hq / a.Hkv;
   const int R = G * a.n_q;
   const int g = h / G, r = i * G + h % G;
   const int total = a.ctx_len[b] + a.n_q;
   const int nact = (total + a.chunk - 1) / a.chunk;
   const size_t unit0 = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit;
+  const float* ml = a.part_ml + (unit0 * R + r) * 2;          // chunk s at ml[s * R * 2]
+  const float* po = a.part_o + (unit0 * R + r) * D + lane * PER;  // chunk s at po[s * R * D]
   float mmax = -INFINITY;
-  for (int s = 0; s < nact; ++s) mmax = fmaxf(mmax, a.part_ml[((unit0 + s) * R + r) * 2]);
-  float den = 0.f, num = 0.f;
-  for (int s = 0; s < nact; ++s) {
-    const float ms = a.part_ml[((unit0 + s) * R + r) * 2];
-    if (ms == -INFINITY) continue;
-    const float w = a.use_mfma ? exp2f(ms - mmax) : expf(ms - mmax);
-    den = fmaf(w, a.part_ml[((unit0 + s) * R + r) * 2 + 1], den);
-    num = fmaf(w, a.part_o[((unit0 + s) * R + r) * a.d + c], num);
+  for (int s = lane; s < nact; s += 64) mmax = fmaxf(mmax, ml[static_cast<size_t>(s) * R * 2]);
+  mmax = wave_max(mmax);
+  float den = 0.f;
+  for (int s = lane; s < nact; s += 64) {
+    const float ms = ml[static_cast<size_t>(s) * R * 2];
+    if (ms != -INFINITY) {
+      const float w = a.use_mfma ? exp2f(ms - mmax) : expf(ms - mmax);
+      den = fmaf(w, ml[static_cast<size_t>(s) * R * 2 + 1], den);
+    }
   }
-  T* dst = static_cast<T*>(a.out) + ((static_cast<size_t>(b) * a.n_q + i) * a.Hq + h) * a.d;
-  Elem<T>::store(dst + c, num / den);
+  den = wave_sum(den);
+  float num[PER];
+#pragma unroll
+  for (int e = 0; e < PER; ++e) num[e] = 0.f;
+  for (int s = 0; s < nact; s += 4) {
+    float w[4], o[4][PER];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int ss = min(s + u, nact - 1);
+      const float ms = ml[static_cast<size_t>(ss) * R * 2];
+      w[u] = (s + u < nact && ms != -INFINITY) ? (a.use_mfma ? exp2f(ms - mmax) : expf(ms - mmax)) : 0.f;
+#pragma unroll
+      for (int e = 0; e < PER; ++e) o[u][e] = po[static_cast<size_t>(ss) * R * D + e];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int e = 0; e < PER; ++e) num[e] = fmaf(w[u], w[u] != 0.f ? o[u][e] : 0.f, num[e]);
+  }
+  T* dst = static_cast<T*>(a.out) + ((static_cast<size_t>(b) * a.n_q + i) * a.Hq + h) * D + lane * PER;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) Elem<T>::store(dst + e, num[e] / den);
 }
 
 size_t valu_smem_bytes(const AttnArgs& a) {
@@ -214,15 +240,22 @@ hipError_t launch_valu(const AttnArgs& a, hipStream_t s) {
 }  // namespace
 
 void attn_plan(AttnArgs& a, int num_cus) {
-  // chunk of the cache length handled by one workgroup: enough workgroups to cover the
-  // chip about twice when every sequence is at its longest, never below 128 keys
+  // Chunk of the cache length handled by one workgroup.  The host knows only the upper
+  // bound l_max of the lengths, so the grid is sized for it and workgroups past a sequence's
+  // end leave at once.  Small problems get one workgroup per CU at most (a second round of
+  // workgroups would double their latency); large ones get about three rounds so that
+  // sequences of different length balance out.
+  a.use_mfma = attn_mfma_supported(a) ? 1 : 0;
   const int64_t units = static_cast<int64_t>(a.B) * a.Hkv;
   const int64_t lmax = a.l_max;
-  a.use_mfma = attn_mfma_supported(a) ? 1 : 0;
-  const int64_t target = (a.use_mfma ? 3 : 2) * static_cast<int64_t>(num_cus);
-  int64_t chunk = (units * lmax + target - 1) / target;
+  const int64_t keys = units * lmax;
+  const int64_t rounds = keys >= static_cast<int64_t>(num_cus) * 3 * 1024 ? 3 : 1;
+  const int64_t target = rounds * num_cus;
+  int64_t chunk = (keys + target - 1) / target;
   chunk = ((chunk + 127) / 128) * 128;
   if (chunk < 128) chunk = 128;
+  // never more workgroups than the target: rounding the split count up must not spill over
+  while (units * ((lmax + chunk - 1) / chunk) > target && chunk < lmax) chunk += 128;
   a.chunk = static_cast<int>(chunk);
   a.nsplit = static_cast<int>((lmax + chunk - 1) / chunk);
   if (a.nsplit < 1) a.nsplit = 1;
@@ -250,10 +283,14 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t s, KernelHook hook, int ho
   }
   if (hook) hook(hook_id, 1, s);
   if (e != hipSuccess) return e;
-  if (a.dtype == 1)
-    hipLaunchKernelGGL(k_attn_combine<bf16_t>, dim3(a.Hq, a.n_q, a.B), dim3(a.d), 0, s, a);
-  else
-    hipLaunchKernelGGL(k_attn_combine<float>, dim3(a.Hq, a.n_q, a.B), dim3(a.d), 0, s, a);
+  const dim3 grid(a.Hq, a.n_q, a.B);
+  if (a.dtype == 1) {
+    if (a.d == 128) hipLaunchKernelGGL((k_attn_combine<bf16_t, 128>), grid, dim3(64), 0, s, a);
+    else hipLaunchKernelGGL((k_attn_combine<bf16_t, 64>), grid, dim3(64), 0, s, a);
+  } else {
+    if (a.d == 128) hipLaunchKernelGGL((k_attn_combine<float, 128>), grid, dim3(64), 0, s, a);
+    else hipLaunchKernelGGL((k_attn_combine<float, 64>), grid, dim3(64), 0, s, a);
+  }
   return hipGetLastError();
 }
 

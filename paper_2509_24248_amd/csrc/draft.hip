@@ -9,7 +9,6 @@ namespace sx {
 
 namespace {
 
-constexpr int kMaxGroups = 4;  // 8-element groups per thread: rows up to 4*256*8 = 8192 wide
 
 __device__ __forceinline__ float block_sum_256(float v, float* sh) {
   v = wave_sum(v);
@@ -56,47 +55,72 @@ __global__ __launch_bounds__(256) void k_embed_concat(int D, const T* __restrict
   }
 }
 
+constexpr int kNormThreads = 1024;
+constexpr int kNormIters = 2;   // float4 per thread per iteration: rows up to 2 * 1024 * 4 = 8192 wide
+
 template <typename T>
-__global__ __launch_bounds__(256) void k_reduce_norm(int B, int N, const float* __restrict__ partial,
-                                                     int nslices, int planes,
-                                                     const float* __restrict__ residual,
-                                                     const T* __restrict__ gain, float eps,
-                                                     float* __restrict__ sum_out, T* __restrict__ hidden_out,
-                                                     float* __restrict__ act) {
-  __shared__ float sh[4];
+__global__ __launch_bounds__(kNormThreads) void k_reduce_norm(int B, int N, const float* __restrict__ partial,
+                                                              int nslices, int planes,
+                                                              const float* __restrict__ residual,
+                                                              const T* __restrict__ gain, float eps,
+                                                              float* __restrict__ sum_out, T* __restrict__ hidden_out,
+                                                              float* __restrict__ act) {
+  __shared__ float sh[kNormThreads / 64];
   const int b = blockIdx.x;
-  float vals[kMaxGroups][8];
+  const int Mv = B * planes;
+  const int total = nslices * planes;   // partial rows to add: slice j -> row (j / planes) * Mv + b * planes + j % planes
+  float4 vals[kNormIters];
   float ssq = 0.f;
 #pragma unroll
-  for (int it = 0; it < kMaxGroups; ++it) {
-    const int g8 = threadIdx.x + it * 256;
-    if (g8 < N / 8) {
-      float f[8];
-      gather_partial(partial, nslices, planes, B, N, b, g8 * 8, f);
-      if (residual) {
+  for (int it = 0; it < kNormIters; ++it) {
+    const int n = (threadIdx.x + it * kNormThreads) * 4;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (n < N) {
+      if (residual) acc = *reinterpret_cast<const float4*>(residual + static_cast<size_t>(b) * N + n);
+      int j = 0;
+      for (; j + 4 <= total; j += 4) {
+        float4 v[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) f[e] += residual[static_cast<size_t>(b) * N + g8 * 8 + e];
+        for (int u = 0; u < 4; ++u) {
+          const int jj = j + u;
+          const size_t row = static_cast<size_t>(jj / planes) * Mv + b * planes + jj % planes;
+          v[u] = *reinterpret_cast<const float4*>(partial + row * N + n);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { acc.x += v[u].x; acc.y += v[u].y; acc.z += v[u].z; acc.w += v[u].w; }
       }
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        vals[it][e] = f[e];
-        ssq = fmaf(f[e], f[e], ssq);
-        if (sum_out) sum_out[static_cast<size_t>(b) * N + g8 * 8 + e] = f[e];
-        if (hidden_out) Elem<T>::store(hidden_out + static_cast<size_t>(b) * N + g8 * 8 + e, f[e]);
+      for (; j < total; ++j) {
+        const size_t row = static_cast<size_t>(j / planes) * Mv + b * planes + j % planes;
+        const float4 v = *reinterpret_cast<const float4*>(partial + row * N + n);
+        acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+      }
+      ssq += acc.x * acc.x + acc.y * acc.y + acc.z * acc.z + acc.w * acc.w;
+      if (sum_out) *reinterpret_cast<float4*>(sum_out + static_cast<size_t>(b) * N + n) = acc;
+      if (hidden_out) {
+        T* dst = hidden_out + static_cast<size_t>(b) * N + n;
+        Elem<T>::store(dst + 0, acc.x); Elem<T>::store(dst + 1, acc.y);
+        Elem<T>::store(dst + 2, acc.z); Elem<T>::store(dst + 3, acc.w);
       }
     }
+    vals[it] = acc;
   }
-  const float tot = block_sum_256(ssq, sh);
+  ssq = wave_sum(ssq);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = ssq;
+  __syncthreads();
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < kNormThreads / 64; ++w) tot += sh[w];
   const float rinv = 1.0f / sqrtf(tot / static_cast<float>(N) + eps);
 #pragma unroll
-  for (int it = 0; it < kMaxGroups; ++it) {
-    const int g8 = threadIdx.x + it * 256;
-    if (g8 < N / 8) {
-      float f[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) f[e] = vals[it][e] * rinv * Elem<T>::load(gain + g8 * 8 + e);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) act[static_cast<size_t>(b) * N + g8 * 8 + e] = f[e];
+  for (int it = 0; it < kNormIters; ++it) {
+    const int n = (threadIdx.x + it * kNormThreads) * 4;
+    if (n < N) {
+      float4 o;
+      o.x = vals[it].x * rinv * Elem<T>::load(gain + n + 0);
+      o.y = vals[it].y * rinv * Elem<T>::load(gain + n + 1);
+      o.z = vals[it].z * rinv * Elem<T>::load(gain + n + 2);
+      o.w = vals[it].w * rinv * Elem<T>::load(gain + n + 3);
+      *reinterpret_cast<float4*>(act + static_cast<size_t>(b) * N + n) = o;
     }
   }
 }
@@ -205,10 +229,10 @@ hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* pa
                               int planes, const float* residual, const void* gain, float* sum_out,
                               void* hidden_out, float* act, hipStream_t s) {
   if (dm.dtype == 1)
-    hipLaunchKernelGGL(k_reduce_norm<bf16_t>, dim3(B), dim3(256), 0, s, B, N, partial, nslices, planes, residual,
+    hipLaunchKernelGGL(k_reduce_norm<bf16_t>, dim3(B), dim3(kNormThreads), 0, s, B, N, partial, nslices, planes, residual,
                        static_cast<const bf16_t*>(gain), dm.rms_eps, sum_out, static_cast<bf16_t*>(hidden_out), act);
   else
-    hipLaunchKernelGGL(k_reduce_norm<float>, dim3(B), dim3(256), 0, s, B, N, partial, nslices, planes, residual,
+    hipLaunchKernelGGL(k_reduce_norm<float>, dim3(B), dim3(kNormThreads), 0, s, B, N, partial, nslices, planes, residual,
                        static_cast<const float*>(gain), dm.rms_eps, sum_out, static_cast<float*>(hidden_out), act);
   return hipGetLastError();
 }

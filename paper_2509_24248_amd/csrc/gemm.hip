@@ -270,16 +270,23 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
   }
 }
 
-__global__ __launch_bounds__(256) void k_argmax_finalize(const float* __restrict__ part_val,
-                                                         const int* __restrict__ part_idx, int ntiles,
-                                                         int32_t* __restrict__ argmax,
-                                                         float* __restrict__ max_logit) {
-  __shared__ float sv[4];
-  __shared__ int si[4];
+constexpr int kFinalThreads = 1024;
+
+// One block per activation row: reduce the per-tile (max, index) pairs; for the draft head
+// the same block also turns the three signal logits into signals (Eqs. 3-5).
+__global__ __launch_bounds__(kFinalThreads) void k_argmax_finalize(const float* __restrict__ part_val,
+                                                                   const int* __restrict__ part_idx, int ntiles,
+                                                                   int32_t* __restrict__ argmax,
+                                                                   float* __restrict__ max_logit,
+                                                                   const float* __restrict__ extra,
+                                                                   int rem_activation, float* __restrict__ sig_raw,
+                                                                   float* __restrict__ sig) {
+  __shared__ float sv[kFinalThreads / 64];
+  __shared__ int si[kFinalThreads / 64];
   const int m = blockIdx.x;
   float bv = -INFINITY;
   int bi = INT_MAX;
-  for (int t = threadIdx.x; t < ntiles; t += 256) {
+  for (int t = threadIdx.x; t < ntiles; t += kFinalThreads) {
     const float v = part_val[static_cast<size_t>(m) * ntiles + t];
     const int i = part_idx[static_cast<size_t>(m) * ntiles + t];
     if (better(v, i, bv, bi)) { bv = v; bi = i; }
@@ -293,10 +300,17 @@ __global__ __launch_bounds__(256) void k_argmax_finalize(const float* __restrict
   if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    for (int w = 1; w < 4; ++w)
+    for (int w = 1; w < kFinalThreads / 64; ++w)
       if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
     argmax[m] = bi;
     if (max_logit) max_logit[m] = bv;
+  }
+  if (sig && threadIdx.x == 64) {
+    const float zc = extra[m * 3 + 0], zp = extra[m * 3 + 1], zr = extra[m * 3 + 2];
+    sig_raw[m * 3 + 0] = zc; sig_raw[m * 3 + 1] = zp; sig_raw[m * 3 + 2] = zr;
+    sig[m * 3 + 0] = sigmoidf_(zc);
+    sig[m * 3 + 1] = sigmoidf_(zp);
+    sig[m * 3 + 2] = rem_activation == 0 ? fmaxf(0.f, expm1f(zr)) : (rem_activation == 1 ? sigmoidf_(zr) : zr);
   }
 }
 
@@ -425,8 +439,10 @@ hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
 }
 
 hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, int ntiles, int M,
-                                  int32_t* argmax, float* max_logit, hipStream_t s) {
-  hipLaunchKernelGGL(k_argmax_finalize, dim3(M), dim3(256), 0, s, part_val, part_idx, ntiles, argmax, max_logit);
+                                  int32_t* argmax, float* max_logit, hipStream_t s, const float* extra,
+                                  int rem_activation, float* sig_raw, float* sig) {
+  hipLaunchKernelGGL(k_argmax_finalize, dim3(M), dim3(kFinalThreads), 0, s, part_val, part_idx, ntiles, argmax,
+                     max_logit, extra, rem_activation, sig_raw, sig);
   return hipGetLastError();
 }
 

@@ -44,8 +44,11 @@ void choose_ksplit(GemmArgs& g, bool mfma);
 hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
 // reduce per-tile partial argmaxes: one result per activation row
+// (with `sig` set it also applies the signal activations to extra[M][3]: the draft head's epilogue)
 hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, int ntiles, int M,
-                                  int32_t* argmax, float* max_logit, hipStream_t s);
+                                  int32_t* argmax, float* max_logit, hipStream_t s,
+                                  const float* extra = nullptr, int rem_activation = 0,
+                                  float* sig_raw = nullptr, float* sig = nullptr);
 // VALU head path: logits [M][N] -> argmax over n < V, copy of signal rows and of logits
 hipError_t launch_argmax_rows(const float* logits, int M, int N, int V, int n_extra,
                               int32_t* argmax, float* max_logit, float* extra_out,
