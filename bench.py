@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run the library's copy kernel over the head weights (both load paths) once, "
+                         "so that a counter-collecting profiler run holds a kernel of known traffic")
     return ap.parse_args()
 
 
@@ -171,12 +174,15 @@ def threads_used():
 
 def stored_traffic(shape_name):
     """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_head_gemm_{shape_name}.json")
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_head_gemm_{shape_name}.txt")
     try:
         with open(path) as fh:
-            return json.load(fh).get("bytes_per_launch")
+            for line in fh:
+                if line.startswith("bytes_per_launch"):
+                    return int(line.split()[1])
     except Exception:
-        return None
+        pass
+    return None
 
 
 def main():
@@ -197,6 +203,14 @@ def main():
     for _ in range(max(args.warmup, 1)):
         rnd.run()
     torch.cuda.synchronize()
+    if args.copy_probe:
+        src = rnd.wt["w_head"]
+        dst = torch.empty_like(src)
+        nbytes = (src.numel() * src.element_size()) // 16 * 16
+        for nt in (False, True):
+            sx.specexit_copy_probe(src, dst, nbytes, nt)
+        torch.cuda.synchronize()
+        del dst
 
     # ---- eager leg with per-kernel events: duration of the dominant kernel, live
     K = args.steps

@@ -195,6 +195,12 @@ int32_t specexit_accept_exit(const specexit_exit_cfg *cfg, int32_t B, int32_t n_
 int32_t specexit_profile_events(int32_t kernel, void *const *start_events, void *const *stop_events,
                                 int32_t n);
 
+/* Copies `bytes` (a multiple of 16; both pointers 16-byte aligned, device memory, no overlap)
+ * with 16-byte loads: non-temporal ones, as the weight and KV streams use, when nontemporal
+ * != 0, ordinary ones otherwise.  A plain kernel of known traffic: profiler byte counters
+ * read for the library's kernels are scaled by what they read for this one. */
+int32_t specexit_copy_probe(const void *src, void *dst, size_t bytes, int32_t nontemporal, void *stream);
+
 const char *specexit_last_error(void); /* [host] thread-local, never NULL */
 uint32_t specexit_version(void);
 

@@ -24,7 +24,7 @@ EXPORTS = [
     "specexit_draft_step", "specexit_draft_step_workspace_bytes",
     "specexit_verify_attn", "specexit_verify_attn_workspace_bytes",
     "specexit_lmhead_argmax", "specexit_lmhead_argmax_workspace_bytes",
-    "specexit_accept_exit", "specexit_last_error", "specexit_version", "specexit_profile_events",
+    "specexit_accept_exit", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
 
@@ -88,6 +88,8 @@ def _load() -> C.CDLL:
     lib.specexit_accept_exit.restype = i32
     lib.specexit_accept_exit.argtypes = [C.POINTER(ExitCfg), i32, i32, vp, vp, vp, vp, vp, vp, i32,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+    lib.specexit_copy_probe.restype = i32
+    lib.specexit_copy_probe.argtypes = [vp, vp, sz, i32, vp]
     lib.specexit_profile_events.restype = i32
     lib.specexit_profile_events.argtypes = [i32, C.POINTER(vp), C.POINTER(vp), i32]
     return lib
@@ -244,3 +246,7 @@ def specexit_profile_events(kernel: int, start_events=None, stop_events=None) ->
 
 def specexit_profile_events_used(kernel: int) -> int:
     return int(LIB.specexit_profile_events(kernel, None, None, -1))
+
+
+def specexit_copy_probe(src, dst, nbytes: int, nontemporal: bool, stream=None) -> None:
+    _check(LIB.specexit_copy_probe(_ptr(src), _ptr(dst), nbytes, 1 if nontemporal else 0, _stream(stream)))

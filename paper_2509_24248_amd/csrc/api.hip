@@ -259,6 +259,12 @@ extern "C" {
 
 const char* specexit_last_error(void) { return g_err; }
 
+int32_t specexit_copy_probe(const void* src, void* dst, size_t bytes, int32_t nontemporal, void* stream) {
+  if (!src || !dst || bytes < 16 || (bytes & 15)) return fail(SPECEXIT_EINVAL, "copy_probe: null pointer or size not a multiple of 16");
+  if ((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) return fail(SPECEXIT_EINVAL, "copy_probe: pointers must be 16-byte aligned");
+  return check_hip(launch_copy_probe(src, dst, bytes, nontemporal != 0, static_cast<hipStream_t>(stream)), "copy_probe");
+}
+
 int32_t specexit_profile_events(int32_t kernel, void* const* start_events, void* const* stop_events, int32_t n) {
   if (kernel < 0 || kernel > 3) return fail(SPECEXIT_EINVAL, "profile_events: unknown kernel id %d", kernel);
   ProfSlot& sl = g_prof[kernel];

@@ -107,6 +107,9 @@ hipError_t launch_head_finalize(const DraftDims& dm, int B, const int32_t* argma
                                 const float* extra, int32_t* next_tok, float* sig_raw, float* sig,
                                 hipStream_t s);
 
+// ---- measurement aid: copy of known size through the streaming load path -------------------
+hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, bool nontemporal, hipStream_t s);
+
 // ---- controller ------------------------------------------------------------------------
 struct ExitArgs {
   float alpha, thr_conf, thr_prog, thr_rem;
