@@ -256,6 +256,7 @@ void attn_plan(AttnArgs& a, int num_cus) {
   if (chunk < 128) chunk = 128;
   // never more workgroups than the target: rounding the split count up must not spill over
   while (units * ((lmax + chunk - 1) / chunk) > target && chunk < lmax) chunk += 128;
+  if (a.use_mfma && chunk > attn_mfma_max_chunk(a)) chunk = attn_mfma_max_chunk(a) / 128 * 128;
   a.chunk = static_cast<int>(chunk);
   a.nsplit = static_cast<int>((lmax + chunk - 1) / chunk);
   if (a.nsplit < 1) a.nsplit = 1;

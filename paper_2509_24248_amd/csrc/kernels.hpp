@@ -77,6 +77,7 @@ struct AttnArgs {
   int use_mfma;              // matrix-core kernel (bf16, head_dim 128); its maxima are in log2 units
 };
 bool attn_mfma_supported(const AttnArgs& a);
+int attn_mfma_max_chunk(const AttnArgs& a);   // longest chunk the matrix-core kernel takes
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
 void attn_plan(AttnArgs& a, int num_cus);
 size_t attn_workspace_bytes(const AttnArgs& a);
