@@ -42,6 +42,17 @@ constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | (((n >> 4) & 3) << 1
 // the compiler does not put a full vector-memory wait in front of every later LDS read; the
 // kernel paces these loads itself with s_waitcnt vmcnt and a barrier.  "nt" marks the stream
 // as read-once.  m0 is written here and used by nothing else in these kernels.
+// Same with a wave-uniform 64-bit base and a 32-bit per-lane byte offset.
+__device__ __forceinline__ void load_to_lds16(const void* base, uint32_t off, const void* lds_base) {
+  const uint32_t l = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)lds_base));
+  const uint64_t b64 = reinterpret_cast<uint64_t>(base);   // uniform by construction: pin it to scalar registers
+  // (readfirstlane returns a signed int: go through uint32_t so the low half is not sign-extended)
+  const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b64))));
+  const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(b64 >> 32))));
+  const uint64_t sb = static_cast<uint64_t>(lo) | (static_cast<uint64_t>(hi) << 32);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(l), "v"(off), "s"(sb) : "memory");
+}
+
 __device__ __forceinline__ void load_to_lds16(const void* src, const void* lds_base) {
   const uint32_t l = static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_ptr_t)lds_base));
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(l), "v"(src) : "memory");
@@ -97,7 +108,17 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));    // from here on vmcnt counts tile loads only
   __syncthreads();
 
-  // ---- tile loads: the ring's waves take the 16 one-KB pieces of a tile in turn
+  // ---- tile loads: the ring's waves take the 16 one-KB pieces of a tile in turn.  Piece j
+  // holds keys 4 (j % 8) .. + 3; lane l fetches key 4 (j % 8) + l / 16, 16-byte chunk
+  // (l % 16) ^ (key % 16), and lands at piece base + 16 l, so that LDS entry [key][pos] holds
+  // chunk pos ^ (key % 16).  The lane's byte offset inside a tile does not depend on the tile.
+  uint32_t lane_off[(16 + NR - 1) / NR];
+#pragma unroll
+  for (int u = 0; u < (16 + NR - 1) / NR; ++u) {
+    const int key = 4 * ((rr + u * NR) & 7) + fq;
+    const int in_row = PAGED ? (key & (a.page_size - 1)) : key;
+    lane_off[u] = static_cast<uint32_t>(in_row) * 256u + static_cast<uint32_t>((fr ^ (key & 15)) << 4);
+  }
   const size_t seq_row = PAGED ? 0 : (static_cast<size_t>(b) * a.Hkv + g) * a.l_max;
   auto issue = [&](int it) {
     const int ti = it * kNK + kg;
@@ -115,10 +136,24 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
     } else {
       row_a = row_b = seq_row;
     }
+    if (t0 + 32 <= s1) {
+      // whole tile inside the range: uniform base per piece + the lane's constant offset
+      const size_t in_page = PAGED ? static_cast<size_t>(t0 & (a.page_size - 1)) : static_cast<size_t>(t0);
+#pragma unroll
+      for (int u = 0; u < (16 + NR - 1) / NR; ++u) {
+        const int j = rr + u * NR;             // piece: 0..7 K keys 4j.., 8..15 V keys 4(j-8)..
+        if (j < 16) {
+          const bool second = PAGED && a.page_size == 16 && (j & 4);   // keys 16..31 sit in the next page
+          const char* base = static_cast<const char*>(j < 8 ? a.k : a.v) + ((second ? row_b : row_a) + in_page) * 256;
+          load_to_lds16(base, lane_off[u], slot + j * 1024);
+        }
+      }
+      return;
+    }
     const int page0 = t0 >> ps_shift;
 #pragma unroll
     for (int u = 0; u < (16 + NR - 1) / NR; ++u) {
-      const int j = rr + u * NR;               // piece: 0..7 K rows 4j.., 8..15 V rows
+      const int j = rr + u * NR;
       if (j < 16) {
         const int i = j & 7;
         const int key = 4 * i + fq;
