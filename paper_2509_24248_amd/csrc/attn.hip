@@ -250,7 +250,8 @@ void attn_plan(AttnArgs& a, int num_cus) {
   const int64_t lmax = a.l_max;
   const int64_t keys = units * lmax;
   const int64_t rounds = keys >= static_cast<int64_t>(num_cus) * 3 * 1024 ? 3 : 1;
-  const int64_t target = rounds * num_cus;
+  const int64_t per_cu = a.use_mfma ? 2 : 1;   // workgroups of the matrix-core kernel that fit a CU
+  const int64_t target = rounds * num_cus * (rounds == 1 ? per_cu : 1);
   int64_t chunk = (keys + target - 1) / target;
   chunk = ((chunk + 127) / 128) * 128;
   if (chunk < 128) chunk = 128;

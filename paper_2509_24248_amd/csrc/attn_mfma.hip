@@ -27,7 +27,7 @@ namespace {
 constexpr int kNK = 2;                 // tile rings (key groups) per workgroup
 constexpr int kSlot = 16384;           // bytes of one ring slot: K tile then V tile
 constexpr int kORow = 132;             // floats per row of the merge buffer (128 + pad)
-constexpr int kMaxChunkPages = 4096;   // page ids of one chunk kept in LDS (16 KB)
+constexpr int kMaxChunkPages = 2048;   // page ids of one chunk kept in LDS (8 KB)
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
@@ -35,6 +35,12 @@ typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
 // s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and
 // 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
+// XOR swizzle of the 16-byte chunks of a tile row.  K rows are read one row per lane (16 rows
+// at once): chunk ^ (key % 16) spreads them over all banks.  V rows are read by the transpose
+// load, 4 rows x 2 adjacent chunks at once: chunk ^ (2 (key % 8)) keeps those eight apart.
+__device__ __forceinline__ int swz_k(int key) { return key & 15; }
+__device__ __forceinline__ int swz_v(int key) { return (key & 7) << 1; }
+
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | (((n >> 4) & 3) << 14); }
 
 // Direct global -> LDS load, 16 bytes per lane: lane l's bytes land at lds_base + 16 l
@@ -110,14 +116,15 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
 
   // ---- tile loads: the ring's waves take the 16 one-KB pieces of a tile in turn.  Piece j
   // holds keys 4 (j % 8) .. + 3; lane l fetches key 4 (j % 8) + l / 16, 16-byte chunk
-  // (l % 16) ^ (key % 16), and lands at piece base + 16 l, so that LDS entry [key][pos] holds
-  // chunk pos ^ (key % 16).  The lane's byte offset inside a tile does not depend on the tile.
+  // (l % 16) ^ swizzle(key), and lands at piece base + 16 l, so that LDS entry [key][pos] holds
+  // chunk pos ^ swizzle(key).  The lane's byte offset inside a tile does not depend on the tile.
   uint32_t lane_off[(16 + NR - 1) / NR];
 #pragma unroll
   for (int u = 0; u < (16 + NR - 1) / NR; ++u) {
     const int key = 4 * ((rr + u * NR) & 7) + fq;
     const int in_row = PAGED ? (key & (a.page_size - 1)) : key;
-    lane_off[u] = static_cast<uint32_t>(in_row) * 256u + static_cast<uint32_t>((fr ^ (key & 15)) << 4);
+    const int sw = ((rr + u * NR) & 8) ? swz_v(key) : swz_k(key);   // pieces 8..15 are V
+    lane_off[u] = static_cast<uint32_t>(in_row) * 256u + static_cast<uint32_t>((fr ^ sw) << 4);
   }
   const size_t seq_row = PAGED ? 0 : (static_cast<size_t>(b) * a.Hkv + g) * a.l_max;
   auto issue = [&](int it) {
@@ -161,8 +168,7 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
         size_t row;
         if (PAGED) row = ((p >> ps_shift) == page0 ? row_a : row_b) + (p & (a.page_size - 1));
         else row = row_a + p;
-        const char* src = static_cast<const char*>(j < 8 ? a.k : a.v) + row * 256 + ((fr ^ (key & 15)) << 4);
-        // lane l lands at piece base + 16 l: LDS entry [key][pos = l % 16] holds 16-byte chunk pos ^ (key % 16)
+        const char* src = static_cast<const char*>(j < 8 ? a.k : a.v) + row * 256 + ((fr ^ (j < 8 ? swz_k(key) : swz_v(key))) << 4);
         load_to_lds16(src, slot + j * 1024);
       }
     }
@@ -258,8 +264,8 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) {
         const int chunk = 2 * dt + (c >> 1);
-        const char* p0 = v_lds + key0 * 256 + ((chunk ^ (key0 & 15)) << 4) + ((c & 1) << 3);
-        const char* p1 = v_lds + key1 * 256 + ((chunk ^ (key1 & 15)) << 4) + ((c & 1) << 3);
+        const char* p0 = v_lds + key0 * 256 + ((chunk ^ swz_v(key0)) << 4) + ((c & 1) << 3);
+        const char* p1 = v_lds + key1 * 256 + ((chunk ^ swz_v(key1)) << 4) + ((c & 1) << 3);
         const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(lds_ptr_t)p0);
         const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(lds_ptr_t)p1);
         const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
@@ -324,7 +330,7 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   }
 }
 
-constexpr int kStages = 4;
+constexpr int kStages = 2;
 
 template <int NR, bool PAGED>
 hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
