@@ -64,13 +64,23 @@ __device__ __forceinline__ void load_to_lds16(const void* src, const void* lds_b
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(l), "v"(src) : "memory");
 }
 
-template <int NR, int S, bool PAGED>
+constexpr int front_bytes(int rp, int stages) {
+  return kNK * stages * kSlot > rp * kORow * 4 ? kNK * stages * kSlot : rp * kORow * 4;
+}
+
+// NR waves per ring, each owning RTW 16-row tiles of the queries (rows 16 (rr RTW + t) ..).
+// RTW = 2 halves the LDS reads per query row (K and V operands are fetched once per wave and
+// used for both row tiles) at the price of fewer, fatter waves: used when R > 64.
+template <int NR, int RTW, int S, bool PAGED>
 __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
-  // LDS: [ring 0: S slots][ring 1: S slots][(max, sum) table for the merge][page ids of the chunk]
+  constexpr int RP = 16 * NR * RTW;             // query rows covered (padded)
+  // LDS: [ring 0: S slots][ring 1: S slots] (later overlaid by the merge buffer [RP][kORow]),
+  // then the (max, sum) table for the merge, then the page ids of the chunk
+  constexpr int kFront = front_bytes(RP, S);
   extern __shared__ uint4 smem4[];
   char* smem = reinterpret_cast<char*>(smem4);
-  float* ml_lds = reinterpret_cast<float*>(smem + kNK * S * kSlot);
-  int* pg_lds = reinterpret_cast<int*>(smem + kNK * S * kSlot + kNK * NR * 16 * 2 * sizeof(float));
+  float* ml_lds = reinterpret_cast<float*>(smem + kFront);
+  int* pg_lds = reinterpret_cast<int*>(smem + kFront + kNK * RP * 2 * sizeof(float));
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kg = wv / NR, rr = wv % NR;
@@ -87,19 +97,21 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   const int fr = lane & 15, fq = lane >> 4;
   char* ring = smem + kg * (S * kSlot);
 
-  // ---- Q^T operand pieces and the mask word of this wave's 16 rows
-  const int rho = 16 * rr + fr;
-  const bool row_valid = rho < R;
-  uint4 qf[4];
-  uint64_t rowmask = 0;
-  {
-    const int i = row_valid ? rho / G : 0;
-    const int hh = row_valid ? rho - i * G : 0;
+  // ---- Q^T operand pieces and the mask words of this wave's rows
+  uint4 qf[4][RTW];
+  uint64_t rowmask[RTW];
+  int rho[RTW];
+#pragma unroll
+  for (int t = 0; t < RTW; ++t) {
+    rho[t] = 16 * (rr * RTW + t) + fr;
+    const bool valid = rho[t] < R;
+    const int i = valid ? rho[t] / G : 0;
+    const int hh = valid ? rho[t] - i * G : 0;
     const bf16_t* qp = static_cast<const bf16_t*>(a.q) + ((static_cast<size_t>(b) * a.n_q + i) * a.Hq + g * G + hh) * 128 + fq * 8;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
-      qf[ks] = row_valid ? *reinterpret_cast<const uint4*>(qp + ks * 32) : make_uint4(0, 0, 0, 0);
-    if (row_valid) rowmask = a.mask ? a.mask[static_cast<size_t>(b) * a.n_q + i] : ((2ull << i) - 1ull);
+      qf[ks][t] = valid ? *reinterpret_cast<const uint4*>(qp + ks * 32) : make_uint4(0, 0, 0, 0);
+    rowmask[t] = !valid ? 0ull : (a.mask ? a.mask[static_cast<size_t>(b) * a.n_q + i] : ((2ull << i) - 1ull));
   }
 
   // ---- page ids of the chunk, copied to LDS once: loads from there do not count against
@@ -175,10 +187,15 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   };
   constexpr int kPiecesMin = 16 / NR;          // pieces every wave of a ring issues per tile, at least
 
-  f32x4_t oacc[8];
+  f32x4_t oacc[8][RTW];
+  float m_run[RTW], l_run[RTW];
 #pragma unroll
-  for (int dt = 0; dt < 8; ++dt) oacc[dt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.f;
+  for (int t = 0; t < RTW; ++t) {
+    m_run[t] = -INFINITY;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) oacc[dt][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  }
   const float sl2 = a.scale * 1.44269504088896340736f;  // scores are kept in log2 units
 
 #pragma unroll
@@ -187,7 +204,7 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   for (int it = 0; it < nit; ++it) {
     // this wave's pieces of tile `it` have landed once at most the pieces of the S-2 tiles
     // issued after it are outstanding (loads return in order); near the end simply wait for all
-    if (it + S - 1 < nit) __builtin_amdgcn_s_waitcnt(vmcnt_imm((S - 2) * kPiecesMin));
+    if (S > 2 && it + S - 1 < nit) __builtin_amdgcn_s_waitcnt(vmcnt_imm((S - 2) * kPiecesMin));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     // plain barrier (no memory fence: a fence would wait for the loads still in flight); the
     // wave-scope fences only keep the compiler from moving LDS accesses across it
@@ -202,56 +219,74 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
     const char* v_lds = k_lds + 8192;
 
     // ---- S^T = K Q^T for the two 16-key halves
-    f32x4_t sacc[2] = {f32x4_t{0.f, 0.f, 0.f, 0.f}, f32x4_t{0.f, 0.f, 0.f, 0.f}};
+    f32x4_t sacc[2][RTW];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int t = 0; t < RTW; ++t) sacc[j][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
         const uint4 kf = reinterpret_cast<const uint4*>(k_lds)[(16 * j + fr) * 16 + ((4 * ks + fq) ^ fr)];
-        sacc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf),
-                                                         __builtin_bit_cast(bf16x8_t, qf[ks]), sacc[j], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < RTW; ++t)
+          sacc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf),
+                                                              __builtin_bit_cast(bf16x8_t, qf[ks][t]), sacc[j][t], 0, 0, 0);
       }
 
     // ---- online softmax; lane (row, q) owns keys t0 + 16 j + 4 q + e of its row
-    float x[8];
+    const bool need_mask = t0 + 32 > min(L, s1);
+    uint4 pf[RTW];
+    float alpha[RTW];
+    bool rescale = false;
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x[4 * j + e] = sacc[j][e] * sl2;
-    if (t0 + 32 > min(L, s1)) {
+    for (int t = 0; t < RTW; ++t) {
+      float x[8];
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int p = t0 + 16 * j + 4 * fq + e;
-          bool vis = p < s1;
-          if (vis && p >= L) vis = (rowmask >> (p - L)) & 1ull;
-          if (!vis) x[4 * j + e] = -INFINITY;
-        }
-    }
-    float mt = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-    mt = fmaxf(mt, __shfl_xor(mt, 16, 64));
-    mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
-    const float m_new = fmaxf(m_run, mt);
-    float al = 1.f;
-    float pr[8];
-    if (m_new == -INFINITY) {
+        for (int e = 0; e < 4; ++e) x[4 * j + e] = sacc[j][t][e] * sl2;
+      if (need_mask) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pr[e] = 0.f;
-    } else {
-      al = __builtin_amdgcn_exp2f(m_run - m_new);
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pr[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
-    }
-    const uint4 pf = make_uint4(pack_bf16x2(pr[0], pr[1]), pack_bf16x2(pr[2], pr[3]), pack_bf16x2(pr[4], pr[5]),
-                                pack_bf16x2(pr[6], pr[7]));
-    l_run = l_run * al + (((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7])));
-    m_run = m_new;
-    if (__builtin_amdgcn_ballot_w64(al != 1.f) != 0ull) {
-#pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        oacc[dt][0] *= al; oacc[dt][1] *= al; oacc[dt][2] *= al; oacc[dt][3] *= al;
+          for (int e = 0; e < 4; ++e) {
+            const int p = t0 + 16 * j + 4 * fq + e;
+            bool vis = p < s1;
+            if (vis && p >= L) vis = (rowmask[t] >> (p - L)) & 1ull;
+            if (!vis) x[4 * j + e] = -INFINITY;
+          }
       }
+      float mt = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+      mt = fmaxf(mt, __shfl_xor(mt, 16, 64));
+      mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      const float m_new = fmaxf(m_run[t], mt);
+      float al = 1.f;
+      float pr[8];
+      if (m_new == -INFINITY) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pr[e] = 0.f;
+      } else {
+        al = __builtin_amdgcn_exp2f(m_run[t] - m_new);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pr[e] = __builtin_amdgcn_exp2f(x[e] - m_new);
+      }
+      pf[t] = make_uint4(pack_bf16x2(pr[0], pr[1]), pack_bf16x2(pr[2], pr[3]), pack_bf16x2(pr[4], pr[5]),
+                         pack_bf16x2(pr[6], pr[7]));
+      l_run[t] = l_run[t] * al + (((pr[0] + pr[1]) + (pr[2] + pr[3])) + ((pr[4] + pr[5]) + (pr[6] + pr[7])));
+      m_run[t] = m_new;
+      alpha[t] = al;
+      rescale = rescale || (al != 1.f);
+    }
+    if (__builtin_amdgcn_ballot_w64(rescale) != 0ull) {
+#pragma unroll
+      for (int t = 0; t < RTW; ++t)
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          oacc[dt][t][0] *= alpha[t]; oacc[dt][t][1] *= alpha[t];
+          oacc[dt][t][2] *= alpha[t]; oacc[dt][t][3] *= alpha[t];
+        }
     }
 
     // ---- O^T += V^T P^T.  Transpose load: within 16 lanes, lane i = 4 e + c points at key
@@ -270,56 +305,63 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
         const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(lds_ptr_t)p1);
         const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
         const bf16x8_t va = __builtin_bit_cast(bf16x8_t, make_uint4(l2.x, l2.y, h2.x, h2.y));
-        oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8_t, pf), oacc[dt], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < RTW; ++t)
+          oacc[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8_t, pf[t]), oacc[dt][t], 0, 0, 0);
       }
     }
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 
-  // ---- merge the two rings of each row tile in a fixed order, then one partial per workgroup
-  float* o_lds = reinterpret_cast<float*>(smem);   // merge buffer [16 NR][kORow], overlays the rings
-  {
-    float l = l_run;
+  // ---- merge the two rings of each row in a fixed order, then one partial per workgroup
+  float* o_lds = reinterpret_cast<float*>(smem);   // merge buffer [RP][kORow], overlays the rings
+#pragma unroll
+  for (int t = 0; t < RTW; ++t) {
+    float l = l_run[t];
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
-    l_run = l;
     if (fq == 0) {
-      ml_lds[((kg * NR + rr) * 16 + fr) * 2 + 0] = m_run;
-      ml_lds[((kg * NR + rr) * 16 + fr) * 2 + 1] = l;
+      ml_lds[(kg * RP + rho[t]) * 2 + 0] = m_run[t];
+      ml_lds[(kg * RP + rho[t]) * 2 + 1] = l;
     }
   }
   __syncthreads();   // also: every wave is done with the rings
   const size_t unit = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit + split;
-  float fself = 0.f;
-  {
+  float fself[RTW];
+#pragma unroll
+  for (int t = 0; t < RTW; ++t) {
     float mm = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < kNK; ++w) mm = fmaxf(mm, ml_lds[((w * NR + rr) * 16 + fr) * 2]);
+    for (int w = 0; w < kNK; ++w) mm = fmaxf(mm, ml_lds[(w * RP + rho[t]) * 2]);
     float lt = 0.f;
+    fself[t] = 0.f;
 #pragma unroll
     for (int w = 0; w < kNK; ++w) {
-      const float mw = ml_lds[((w * NR + rr) * 16 + fr) * 2];
+      const float mw = ml_lds[(w * RP + rho[t]) * 2];
       const float fw = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm);
-      lt = fmaf(fw, ml_lds[((w * NR + rr) * 16 + fr) * 2 + 1], lt);
-      if (w == kg) fself = fw;
+      lt = fmaf(fw, ml_lds[(w * RP + rho[t]) * 2 + 1], lt);
+      if (w == kg) fself[t] = fw;
     }
-    if (kg == 0 && fq == 0 && row_valid) {
-      a.part_ml[(unit * R + rho) * 2 + 0] = mm;
-      a.part_ml[(unit * R + rho) * 2 + 1] = lt;
+    if (kg == 0 && fq == 0 && rho[t] < R) {
+      a.part_ml[(unit * R + rho[t]) * 2 + 0] = mm;
+      a.part_ml[(unit * R + rho[t]) * 2 + 1] = lt;
     }
   }
   for (int w = 0; w < kNK; ++w) {
     if (kg == w) {
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        float4* dst = reinterpret_cast<float4*>(o_lds + rho * kORow + 16 * dt + 4 * fq);
-        float4 v = make_float4(oacc[dt][0] * fself, oacc[dt][1] * fself, oacc[dt][2] * fself, oacc[dt][3] * fself);
-        if (w != 0) {
-          const float4 o = *dst;
-          v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+      for (int t = 0; t < RTW; ++t)
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+          float4* dst = reinterpret_cast<float4*>(o_lds + rho[t] * kORow + 16 * dt + 4 * fq);
+          float4 v = make_float4(oacc[dt][t][0] * fself[t], oacc[dt][t][1] * fself[t], oacc[dt][t][2] * fself[t],
+                                 oacc[dt][t][3] * fself[t]);
+          if (w != 0) {
+            const float4 o = *dst;
+            v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+          }
+          *dst = v;
         }
-        *dst = v;
-      }
     }
     __syncthreads();
   }
@@ -332,24 +374,25 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
 
 constexpr int kStages = 2;
 
-template <int NR, bool PAGED>
+template <int NR, int RTW, bool PAGED>
 hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
+  static_assert(NR * RTW <= 8, "at most 128 query rows");
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_ring<NR, kStages, PAGED>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_ring<NR, RTW, kStages, PAGED>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const size_t smem = static_cast<size_t>(kNK) * kStages * kSlot + static_cast<size_t>(kNK) * NR * 16 * 2 * sizeof(float) +
+  const size_t smem = static_cast<size_t>(front_bytes(16 * NR * RTW, kStages)) + static_cast<size_t>(kNK) * NR * RTW * 16 * 2 * sizeof(float) +
                       (PAGED ? static_cast<size_t>(kMaxChunkPages + 1) * sizeof(int) : 0);
-  hipLaunchKernelGGL((k_attn_ring<NR, kStages, PAGED>), dim3(a.nsplit, a.Hkv, a.B), dim3(64 * kNK * NR), smem, s, a);
+  hipLaunchKernelGGL((k_attn_ring<NR, RTW, kStages, PAGED>), dim3(a.nsplit, a.Hkv, a.B), dim3(64 * kNK * NR), smem, s, a);
   return hipGetLastError();
 }
 
-template <int NR>
+template <int NR, int RTW>
 hipError_t launch_nr(const AttnArgs& a, hipStream_t s) {
-  return a.paged ? launch_one<NR, true>(a, s) : launch_one<NR, false>(a, s);
+  return a.paged ? launch_one<NR, RTW, true>(a, s) : launch_one<NR, RTW, false>(a, s);
 }
 
 }  // namespace
@@ -366,14 +409,14 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
   const int R = (a.Hq / a.Hkv) * a.n_q;
   if (a.paged && a.chunk > kMaxChunkPages * a.page_size) return hipErrorInvalidValue;
   switch ((R + 15) / 16) {
-    case 1: return launch_nr<1>(a, s);
-    case 2: return launch_nr<2>(a, s);
-    case 3: return launch_nr<3>(a, s);
-    case 4: return launch_nr<4>(a, s);
-    case 5: return launch_nr<5>(a, s);
-    case 6: return launch_nr<6>(a, s);
-    case 7: return launch_nr<7>(a, s);
-    case 8: return launch_nr<8>(a, s);
+    case 1: return launch_nr<1, 1>(a, s);
+    case 2: return launch_nr<2, 1>(a, s);
+    case 3: return launch_nr<3, 1>(a, s);
+    case 4: return launch_nr<4, 1>(a, s);
+    case 5: return launch_nr<5, 1>(a, s);
+    case 6: return launch_nr<6, 1>(a, s);
+    case 7: return launch_nr<7, 1>(a, s);
+    case 8: return launch_nr<8, 1>(a, s);
     default: return hipErrorInvalidValue;
   }
 }
