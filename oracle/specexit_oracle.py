@@ -17,7 +17,9 @@ What is computed (SpecExit, arXiv 2509.24248):
                     Alg. 1 "target model recover token".
 * accept_exit     - accepted tokens / accept length / recover token (Alg. 1),
                     EWMA smoothing (Sec. 3.3 "Signal Smoothing", Appendix
-                    "Signal Smoothing" EWMA equation, alpha = 0.1), the stop
+                    "Signal Smoothing" EWMA equation, alpha = 0.1; the sliding
+                    window, momentum and paragraph-mean smoothers of the same
+                    appendix, N = 10, as alternatives), the stop
                     thresholds (Appendix "Stop Threshold") and the step-split
                     gate with truncation (Sec. 3.3 "Stopping Conditions",
                     Alg. 1 inner if-block).
@@ -83,8 +85,7 @@ def verify_attn(q, k, v, ctx_len, mask=None, scale=None, page_table=None, page_s
     [n_pages, Hkv, page_size, d] (+ page_table [B, max_pages]); ctx_len [B];
     mask [B, n_q] uint64 (None = chain).  The block's own K/V sit at cache
     positions L_b .. L_b+n_q-1.  Query head h reads KV head h // (Hq/Hkv).
-    Returns out [B, n_q, Hq, d] float64 (entries not in `only` stay NaN) and
-    the softmax rows' sums for the invariant test."""
+    Returns out [B, n_q, Hq, d] float64 (entries not in `only` stay NaN)."""
     q = np.asarray(q)
     B, n_q, Hq, d = q.shape
     Hkv = k.shape[1]
@@ -282,7 +283,8 @@ class ExitCfg:
     thr_prog: float = 0.3
     thr_rem: float = 200.0
     signal_mask: int = 0b111    # bit 0 confidence, 1 progress, 2 remaining
-    smoother: int = 0           # 0 EWMA, 1 none (raw signal)
+    smoother: int = 0           # 0 EWMA, 1 none, 2 sliding window, 3 momentum, 4 paragraph mean
+    window: int = 10            # N of the sliding-window and momentum smoothers (Appendix)
     split_pick: int = 0         # 0 earliest split token in the accepted path, 1 latest
     check_root: int = 0         # also look at the block root (not an accepted draft token)
     stop_think_token: int = 0
@@ -291,6 +293,63 @@ class ExitCfg:
 def ewma_update(x_prev: float, s: float, alpha: float) -> float:
     """x_t = alpha s_t + (1 - alpha) x_{t-1}   (Appendix, EWMA)."""
     return alpha * s + (1.0 - alpha) * x_prev
+
+
+SMOOTH_EWMA, SMOOTH_NONE, SMOOTH_WINDOW, SMOOTH_MOMENTUM, SMOOTH_PARAGRAPH = 0, 1, 2, 3, 4
+
+
+@dataclass
+class SignalHistory:
+    """Everything one sequence has observed while thinking: `values[i]` is the
+    3-vector of round i, `par_start` the index of the first round of the
+    current paragraph (a paragraph ends in a round that accepts a step-split
+    token without leaving thinking)."""
+    values: list
+    par_start: int = 0
+
+
+def new_histories(B: int):
+    return [SignalHistory(values=[]) for _ in range(B)]
+
+
+def smooth_series(s: Sequence[float], cfg: ExitCfg, par_start: int = 0) -> float:
+    """Smoothed score after the observations s[0..t] of one signal, s[t] being
+    this round's (Appendix "Signal Smoothing").
+
+    none       the latest observation.
+    EWMA       x_0 = s_0, then x_i = alpha s_i + (1 - alpha) x_{i-1}.
+    window     mean of the last N observations.
+    momentum   forecast of the next score: the latest observation plus the mean
+               of the N-1 differences between the last N consecutive
+               observations.  (The paper indexes the forecast by the step it
+               predicts, so its s_{t-1} is the latest value seen here.)
+    paragraph  mean of every observation of the current paragraph,
+               s[par_start..t].
+    While fewer than N observations exist, window and momentum use those there
+    are (a single observation is its own forecast); the paper does not say."""
+    s = [float(v) for v in s]
+    t = len(s)
+    assert t >= 1
+    if cfg.smoother == SMOOTH_NONE:
+        return s[-1]
+    if cfg.smoother == SMOOTH_EWMA:
+        x = s[0]
+        for v in s[1:]:
+            x = ewma_update(x, v, cfg.alpha)
+        return x
+    if cfg.smoother == SMOOTH_WINDOW:
+        last = s[-min(cfg.window, t):]
+        return sum(last) / len(last)
+    if cfg.smoother == SMOOTH_MOMENTUM:
+        last = s[-min(cfg.window, t):]
+        if len(last) == 1:
+            return last[0]
+        diffs = [last[i] - last[i - 1] for i in range(1, len(last))]
+        return last[-1] + sum(diffs) / len(diffs)
+    if cfg.smoother == SMOOTH_PARAGRAPH:
+        seg = s[par_start:]
+        return sum(seg) / len(seg)
+    raise ValueError(f"unknown smoother {cfg.smoother}")
 
 
 def greedy_accept(block_tok, parent, a):
@@ -327,12 +386,15 @@ def signals_pass(x, cfg: ExitCfg) -> bool:
 
 
 def accept_exit(cfg: ExitCfg, block_tok, parent, target_argmax, sig, ctx_len, split_tok,
-                ewma, n_obs, is_thinking):
+                ewma, n_obs, is_thinking, hist=None):
     """Per sequence, one decode round of the controller (Alg. 1).
 
-    State (ewma [B,3], n_obs [B], is_thinking [B]) is updated in place.
+    State (ewma [B,3] = the smoothed scores, n_obs [B], is_thinking [B], and for the
+    window / momentum / paragraph smoothers the list `hist` of SignalHistory) is
+    updated in place.
     1. smoothing: the first observation initialises the state, later ones follow
-       the EWMA recurrence; frozen once thinking has ended.
+       the EWMA recurrence (or, with `hist`, smooth_series over the stored
+       observations); frozen once thinking has ended.
     2. acceptance: greedy walk (see greedy_accept); recover token = target argmax
        at the last accepted node.
     3. exit: if thinking, signals pass, and an accepted draft token is a step
@@ -350,12 +412,18 @@ def accept_exit(cfg: ExitCfg, block_tok, parent, target_argmax, sig, ctx_len, sp
     new_ctx = np.zeros(B, np.int32)
     for b in range(B):
         if is_thinking[b]:
-            for j in range(3):
-                s = float(sig[b, j])
-                if cfg.smoother == 1 or n_obs[b] == 0:
-                    ewma[b, j] = s
-                else:
-                    ewma[b, j] = ewma_update(float(ewma[b, j]), s, cfg.alpha)
+            if cfg.smoother in (SMOOTH_EWMA, SMOOTH_NONE):
+                for j in range(3):
+                    s = float(sig[b, j])
+                    if cfg.smoother == SMOOTH_NONE or n_obs[b] == 0:
+                        ewma[b, j] = s
+                    else:
+                        ewma[b, j] = ewma_update(float(ewma[b, j]), s, cfg.alpha)
+            else:
+                h = hist[b]
+                h.values.append([float(sig[b, j]) for j in range(3)])
+                for j in range(3):
+                    ewma[b, j] = smooth_series([v[j] for v in h.values], cfg, h.par_start)
             n_obs[b] += 1
         par = None if parent is None else parent[b]
         path, cur = greedy_accept(block_tok[b], par, target_argmax[b])
@@ -373,6 +441,8 @@ def accept_exit(cfg: ExitCfg, block_tok, parent, target_argmax, sig, ctx_len, sp
             t_rec = int(cfg.stop_think_token)
             is_thinking[b] = 0
             exit_flag[b] = 1
+        elif is_thinking[b] and hit >= 0 and hist is not None:
+            hist[b].par_start = len(hist[b].values)     # a step-split token closed the paragraph
         accept_len[b] = len(path)
         accept_path[b, :len(path)] = path
         recover[b] = t_rec

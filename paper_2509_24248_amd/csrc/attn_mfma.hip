@@ -33,14 +33,14 @@ typedef short s16x4_t __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
-// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and
-// 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
 // XOR swizzle of the 16-byte chunks of a tile row.  K rows are read one row per lane (16 rows
 // at once): chunk ^ (key % 16) spreads them over all banks.  V rows are read by the transpose
 // load, 4 rows x 2 adjacent chunks at once: chunk ^ (2 (key % 8)) keeps those eight apart.
 __device__ __forceinline__ int swz_k(int key) { return key & 15; }
 __device__ __forceinline__ int swz_v(int key) { return (key & 7) << 1; }
 
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and
+// 15:14, expcnt 6:4 and lgkmcnt 11:8 left at their maxima)
 constexpr int vmcnt_imm(int n) { return 0x0F70 | (n & 15) | (((n >> 4) & 3) << 14); }
 
 // Direct global -> LDS load, 16 bytes per lane: lane l's bytes land at lds_base + 16 l
@@ -70,7 +70,8 @@ constexpr int front_bytes(int rp, int stages) {
 
 // NR waves per ring, each owning RTW 16-row tiles of the queries (rows 16 (rr RTW + t) ..).
 // RTW = 2 halves the LDS reads per query row (K and V operands are fetched once per wave and
-// used for both row tiles) at the price of fewer, fatter waves: used when R > 64.
+// used for both row tiles) at the price of fewer, fatter waves; measured slower than RTW = 1
+// at R = 72, so the launcher below uses one row tile per wave throughout.
 template <int NR, int RTW, int S, bool PAGED>
 __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   constexpr int RP = 16 * NR * RTW;             // query rows covered (padded)
