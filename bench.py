@@ -131,7 +131,7 @@ class Round:
         sx.specexit_lmhead_argmax(self.code, s.B * s.n_q, s.D, s.V, 0, self.block_hidden, self.lm,
                                   self.target_argmax, workspace=self.ws_head)
         sx.specexit_accept_exit(self.cfg, s.B, s.n_q, self.block_tok, self.parent, self.target_argmax,
-                                self.sig[0], self.ctx, self.split, self.S, self.ewma, self.n_obs, self.thinking,
+                                self.sig[0], self.ctx, self.split, self.S, self.ewma, self.n_obs, self.thinking, None,
                                 self.accept_len, self.accept_path, self.recover, self.last_node, self.exit_flag,
                                 self.new_ctx)
 

@@ -105,11 +105,21 @@ typedef struct {
   uint32_t struct_size;
   float alpha, thr_conf, thr_prog, thr_rem;
   uint32_t signal_mask;    /* bit 0 confidence, 1 progress, 2 remaining; ANDed */
-  int32_t smoother;        /* 0 EWMA, 1 none (raw signal) */
+  int32_t smoother;        /* SPECEXIT_SMOOTH_*: 0 EWMA, 1 none, 2 sliding window, 3 momentum, 4 paragraph mean */
   int32_t split_pick;      /* 0 earliest step-split token in the accepted path, 1 latest */
   int32_t check_root;      /* 1: the block root may also act as the step-split token */
   int32_t stop_think_token;
+  int32_t window;          /* N of the sliding-window and momentum smoothers, 1..16; 0 = the paper's 10 */
 } specexit_exit_cfg;
+
+/* Smoothers of the Appendix ("Signal Smoothing"). */
+#define SPECEXIT_SMOOTH_EWMA      0
+#define SPECEXIT_SMOOTH_NONE      1
+#define SPECEXIT_SMOOTH_WINDOW    2
+#define SPECEXIT_SMOOTH_MOMENTUM  3
+#define SPECEXIT_SMOOTH_PARAGRAPH 4
+/* 32-bit words of per-sequence history the smoothers 2..4 keep in smooth_state */
+#define SPECEXIT_SMOOTH_WORDS 48
 
 /* ---- stage 1: draft step (Sec. 3.1 Eq. 1; Sec. 3.2 Eqs. 3-5; Alg. 1, first loop line) ----
  * For each of the B rows: x = W_fc [embed[tok] ; hidden_in]; one pre-norm decoder layer
@@ -161,6 +171,12 @@ size_t specexit_lmhead_argmax_workspace_bytes(int32_t dtype, int32_t M, int32_t 
  * Per sequence b:
  *  smoothing  if is_thinking: x = sig on the first observation (n_obs == 0) or when
  *             smoother == 1, else x = alpha*sig + (1-alpha)*x; n_obs += 1.
+ *             Smoothers 2..4 (Appendix, "Signal Smoothing") keep the observations in
+ *             smooth_state: 2 = mean of the last N; 3 = forecast of the next score, the latest
+ *             observation + mean of the N-1 differences between the last N; 4 = mean of all
+ *             observations of the current paragraph, a paragraph ending in a round that accepts
+ *             a step-split token without leaving thinking.  While fewer than N observations
+ *             exist, 2 and 3 use those there are.  x is written to ewma in every mode.
  *  accept     walk from node 0: move to the lowest-index child c of the current node with
  *             block_tok[c] == target_argmax[current]; accept_path lists the nodes entered
  *             (-1 padded), accept_len their number, last_node the final node,
@@ -170,13 +186,16 @@ size_t specexit_lmhead_argmax_workspace_bytes(int32_t dtype, int32_t M, int32_t 
  *             path is cut right after that token (earliest or latest per split_pick),
  *             recover_tok = stop_think_token, is_thinking = 0, exit_flag = 1.
  *  new_ctx_len = ctx_len + 1 + accept_len.
- * ewma [B,3], n_obs [B], is_thinking [B] are in/out state.  split_tok is sorted
- * ascending, S >= 0.  block_tok/parent/target_argmax are [B, n_q]. */
+ * ewma [B,3], n_obs [B], is_thinking [B] are in/out state, and so is smooth_state
+ * [B, SPECEXIT_SMOOTH_WORDS] (32-bit words, zero-filled by the caller when a sequence starts,
+ * opaque afterwards; required for smoothers 2..4, may be NULL otherwise).  split_tok is
+ * sorted ascending, S >= 0.  block_tok/parent/target_argmax are [B, n_q]. */
 int32_t specexit_accept_exit(const specexit_exit_cfg *cfg, int32_t B, int32_t n_q,
                              const int32_t *block_tok, const int32_t *parent,
                              const int32_t *target_argmax, const float *sig /*[B,3]*/,
                              const int32_t *ctx_len /*[B]*/, const int32_t *split_tok, int32_t S,
                              float *ewma, int32_t *n_obs, int32_t *is_thinking,
+                             float *smooth_state /*[B,SPECEXIT_SMOOTH_WORDS] or NULL*/,
                              int32_t *accept_len /*[B]*/, int32_t *accept_path /*[B,n_q]*/,
                              int32_t *recover_tok /*[B]*/, int32_t *last_node /*[B]*/,
                              int32_t *exit_flag /*[B]*/, int32_t *new_ctx_len /*[B]*/,

@@ -27,6 +27,8 @@ EXPORTS = [
     "specexit_accept_exit", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
+SMOOTH_EWMA, SMOOTH_NONE, SMOOTH_WINDOW, SMOOTH_MOMENTUM, SMOOTH_PARAGRAPH = 0, 1, 2, 3, 4
+SMOOTH_WORDS = 48
 
 
 class SpecExitError(RuntimeError):
@@ -61,7 +63,7 @@ class ExitCfg(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("alpha", C.c_float), ("thr_conf", C.c_float),
                 ("thr_prog", C.c_float), ("thr_rem", C.c_float), ("signal_mask", C.c_uint32),
                 ("smoother", C.c_int32), ("split_pick", C.c_int32), ("check_root", C.c_int32),
-                ("stop_think_token", C.c_int32)]
+                ("stop_think_token", C.c_int32), ("window", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -87,7 +89,7 @@ def _load() -> C.CDLL:
     lib.specexit_lmhead_argmax.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
     lib.specexit_accept_exit.restype = i32
     lib.specexit_accept_exit.argtypes = [C.POINTER(ExitCfg), i32, i32, vp, vp, vp, vp, vp, vp, i32,
-                                         vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+                                         vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
     lib.specexit_copy_probe.restype = i32
     lib.specexit_copy_probe.argtypes = [vp, vp, sz, i32, vp]
     lib.specexit_profile_events.restype = i32
@@ -175,9 +177,9 @@ def kv_view(k: torch.Tensor, v: torch.Tensor, page_table: Optional[torch.Tensor]
 
 
 def exit_cfg(alpha=0.1, thr_conf=0.8, thr_prog=0.3, thr_rem=200.0, signal_mask=0b111, smoother=0, split_pick=0,
-             check_root=0, stop_think_token=0) -> ExitCfg:
+             check_root=0, stop_think_token=0, window=0) -> ExitCfg:
     return ExitCfg(C.sizeof(ExitCfg), alpha, thr_conf, thr_prog, thr_rem, signal_mask, smoother, split_pick,
-                   check_root, stop_think_token)
+                   check_root, stop_think_token, window)
 
 
 def _ws_args(ws: Optional[torch.Tensor]):
@@ -222,11 +224,11 @@ def specexit_lmhead_argmax(dtype: int, M: int, D: int, V: int, n_extra: int, hid
 
 
 def specexit_accept_exit(cfg: ExitCfg, B: int, n_q: int, block_tok, parent, target_argmax, sig, ctx_len,
-                         split_tok, S: int, ewma, n_obs, is_thinking, accept_len, accept_path, recover_tok,
-                         last_node, exit_flag, new_ctx_len, flags: int = 0, stream=None) -> None:
+                         split_tok, S: int, ewma, n_obs, is_thinking, smooth_state, accept_len, accept_path,
+                         recover_tok, last_node, exit_flag, new_ctx_len, flags: int = 0, stream=None) -> None:
     _check(LIB.specexit_accept_exit(C.byref(cfg), B, n_q, _ptr(block_tok), _ptr(parent), _ptr(target_argmax),
                                     _ptr(sig), _ptr(ctx_len), _ptr(split_tok), S, _ptr(ewma), _ptr(n_obs),
-                                    _ptr(is_thinking), _ptr(accept_len), _ptr(accept_path), _ptr(recover_tok),
+                                    _ptr(is_thinking), _ptr(smooth_state), _ptr(accept_len), _ptr(accept_path), _ptr(recover_tok),
                                     _ptr(last_node), _ptr(exit_flag), _ptr(new_ctx_len), flags, _stream(stream)))
 
 

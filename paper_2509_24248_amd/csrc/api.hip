@@ -483,7 +483,8 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
 int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_q, const int32_t* block_tok,
                              const int32_t* parent, const int32_t* target_argmax, const float* sig,
                              const int32_t* ctx_len, const int32_t* split_tok, int32_t S, float* ewma,
-                             int32_t* n_obs, int32_t* is_thinking, int32_t* accept_len, int32_t* accept_path,
+                             int32_t* n_obs, int32_t* is_thinking, float* smooth_state, int32_t* accept_len,
+                             int32_t* accept_path,
                              int32_t* recover_tok, int32_t* last_node, int32_t* exit_flag, int32_t* new_ctx_len,
                              uint32_t flags, void* stream) {
   (void)flags;
@@ -492,7 +493,12 @@ int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_
   if (n_q < 1 || n_q > SPECEXIT_MAX_NQ) return fail(SPECEXIT_EINVAL, "accept_exit: n_q %d outside 1..64", n_q);
   if (S < 0 || (S > 0 && !split_tok)) return fail(SPECEXIT_EINVAL, "accept_exit: split token set missing");
   if (!(cfg->alpha >= 0.f && cfg->alpha <= 1.f)) return fail(SPECEXIT_EINVAL, "accept_exit: alpha outside [0,1]");
-  if (cfg->smoother < 0 || cfg->smoother > 1) return fail(SPECEXIT_EUNSUPPORTED, "accept_exit: smoother %d", cfg->smoother);
+  if (cfg->smoother < SPECEXIT_SMOOTH_EWMA || cfg->smoother > SPECEXIT_SMOOTH_PARAGRAPH)
+    return fail(SPECEXIT_EUNSUPPORTED, "accept_exit: smoother %d", cfg->smoother);
+  if (cfg->window < 0 || cfg->window > 16) return fail(SPECEXIT_EINVAL, "accept_exit: window %d outside 1..16 (0 = 10)", cfg->window);
+  if (cfg->smoother >= SPECEXIT_SMOOTH_WINDOW && !smooth_state)
+    return fail(SPECEXIT_EINVAL, "accept_exit: smoother %d needs smooth_state", cfg->smoother);
+  static_assert(kSmoothWords == SPECEXIT_SMOOTH_WORDS, "history size of the ABI and of the kernel differ");
   const void* ptrs[] = {block_tok, target_argmax, sig, ctx_len, ewma, n_obs, is_thinking, accept_len,
                         accept_path, recover_tok, last_node, exit_flag, new_ctx_len};
   for (const void* q : ptrs)
@@ -500,6 +506,7 @@ int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_
   ExitArgs a;
   a.alpha = cfg->alpha; a.thr_conf = cfg->thr_conf; a.thr_prog = cfg->thr_prog; a.thr_rem = cfg->thr_rem;
   a.signal_mask = cfg->signal_mask; a.smoother = cfg->smoother; a.split_pick = cfg->split_pick;
+  a.window = cfg->window ? cfg->window : 10; a.smooth_state = smooth_state;
   a.check_root = cfg->check_root; a.stop_think_token = cfg->stop_think_token;
   a.B = B; a.n_q = n_q; a.S = S;
   a.block_tok = block_tok; a.parent = parent; a.target_argmax = target_argmax; a.sig = sig;

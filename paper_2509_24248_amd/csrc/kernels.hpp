@@ -112,16 +112,18 @@ hipError_t launch_head_finalize(const DraftDims& dm, int B, const int32_t* argma
 hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, bool nontemporal, hipStream_t s);
 
 // ---- controller ------------------------------------------------------------------------
+constexpr int kSmoothWords = 48;   // 3 signals x 16 words
 struct ExitArgs {
   float alpha, thr_conf, thr_prog, thr_rem;
   uint32_t signal_mask;
-  int smoother, split_pick, check_root, stop_think_token;
+  int smoother, window, split_pick, check_root, stop_think_token;
   int B, n_q, S;
   const int32_t *block_tok, *parent, *target_argmax;
   const float* sig;
   const int32_t *ctx_len, *split_tok;
   float* ewma;
   int32_t *n_obs, *is_thinking;
+  float* smooth_state;       // [B][kSmoothWords] history of the window / momentum / paragraph smoothers
   int32_t *accept_len, *accept_path, *recover_tok, *last_node, *exit_flag, *new_ctx_len;
 };
 hipError_t launch_accept_exit(const ExitArgs& a, hipStream_t s);

@@ -161,7 +161,8 @@ def force_draft_gap(shape, w, kv, tok, g, pos, gap=0.05):
 # ----------------------------------------------------------------------------- controller
 
 def gpu_accept_exit(cfg_kwargs, block_tok, parent, target_argmax, sig, ctx_len, split_tok, state):
-    """state = (ewma [B,3] f32, n_obs [B] i32, is_thinking [B] i32) device tensors, updated in place."""
+    """state = (ewma [B,3] f32, n_obs [B] i32, is_thinking [B] i32[, smooth_state [B,48] f32]) device
+    tensors, updated in place."""
     lib = sx()
     B, n_q = block_tok.shape
     cfg = lib.exit_cfg(**cfg_kwargs)
@@ -173,13 +174,17 @@ def gpu_accept_exit(cfg_kwargs, block_tok, parent, target_argmax, sig, ctx_len, 
     lib.specexit_accept_exit(cfg, B, n_q, i32(block_tok), None if parent is None else i32(parent),
                              i32(target_argmax), dev(np.asarray(sig, np.float32), dtype=torch.float32),
                              i32(ctx_len), split, len(split_tok), state[0], state[1], state[2],
+                             state[3] if len(state) > 3 else None,
                              outs["accept_len"], outs["accept_path"], outs["recover_tok"], outs["last_node"],
                              outs["exit_flag"], outs["new_ctx_len"])
     torch.cuda.synchronize()
     return {k: host(v) for k, v in outs.items()}
 
 
-def gpu_state(B):
-    return (torch.zeros((B, 3), dtype=torch.float32, device="cuda"),
-            torch.zeros(B, dtype=torch.int32, device="cuda"),
-            torch.ones(B, dtype=torch.int32, device="cuda"))
+def gpu_state(B, history=False):
+    st = (torch.zeros((B, 3), dtype=torch.float32, device="cuda"),
+          torch.zeros(B, dtype=torch.int32, device="cuda"),
+          torch.ones(B, dtype=torch.int32, device="cuda"))
+    if history:
+        st += (torch.zeros((B, sx().SMOOTH_WORDS), dtype=torch.float32, device="cuda"),)
+    return st

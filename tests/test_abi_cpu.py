@@ -38,7 +38,7 @@ def test_binding_matches_header_and_validates_on_the_host():
     # struct sizes the binding sends equal what the library was compiled with: a wrong size is rejected
     cfg = sx.exit_cfg()
     cfg.struct_size = 4
-    rc = sx.LIB.specexit_accept_exit(ctypes.byref(cfg), 1, 2, *([None] * 6), 0, *([None] * 9), 0, None)
+    rc = sx.LIB.specexit_accept_exit(ctypes.byref(cfg), 1, 2, *([None] * 6), 0, *([None] * 10), 0, None)
     assert rc == sx.EINVAL and b"ABI size" in sx.LIB.specexit_last_error()
     # argument validation happens before any launch: no GPU is needed to see these errors
     assert sx.specexit_lmhead_argmax_workspace_bytes(sx.BF16, 0, 2560, 151936, 0) == 0

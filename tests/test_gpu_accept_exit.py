@@ -97,6 +97,77 @@ def series_with_margin(shape, kw, seed0):
     raise AssertionError("no series with a safe margin found")
 
 
+def conditioned_round(cfg_kw, case, series_t, ctx, ost, hist):
+    """One oracle round on signals nudged, where needed, so that no smoothed value of a thinking
+    sequence lies within 1e-4*max(1,|thr|) of its threshold (float32 on the GPU must not be able to
+    flip a flag).  Input conditioning only: returns the signals used and the oracle's result."""
+    cfg = O.ExitCfg(**cfg_kw)
+    sig = np.array(series_t, dtype=np.float32)
+    thr = (cfg.thr_conf, cfg.thr_prog, cfg.thr_rem)
+    for attempt in range(8):
+        saved = ([a.copy() for a in ost], [(len(h.values), h.par_start) for h in hist])
+        was_thinking = ost[2].copy()
+        ref = O.accept_exit(cfg, case.block_tok, None, case.target_argmax, sig, ctx, case.split_tok, *ost, hist=hist)
+        near = [(b, j) for b in range(sig.shape[0]) if was_thinking[b] for j in range(3)
+                if abs(ost[0][b, j] - thr[j]) < 1e-4 * max(1.0, abs(thr[j]))]
+        if not near:
+            return sig, ref
+        for a, c in zip(ost, saved[0]):
+            a[...] = c
+        for h, (n, p) in zip(hist, saved[1]):
+            del h.values[n:]
+            h.par_start = p
+        for b, j in near:
+            sig[b, j] += np.float32(7e-3 * max(1.0, abs(thr[j])) * (attempt + 1))
+    raise AssertionError("could not move the smoothed signals away from the thresholds")
+
+
+@pytest.mark.parametrize("index", [1, 4])
+@pytest.mark.parametrize("smoother", ["window", "momentum", "paragraph", "window4"])
+def test_other_smoothers_over_many_rounds(index, smoother):
+    """Sliding window, momentum and paragraph mean (Appendix): every round of a whole signal series
+    matches the oracle: integer outputs bit-exact, smoothed values to float32 accuracy."""
+    shape = gen.config(index)
+    kw = dict(stop_think_token=shape.V - 1,
+              smoother={"window": 2, "momentum": 3, "paragraph": 4, "window4": 2}[smoother])
+    if smoother == "window4":
+        kw["window"] = 4
+    rounds = shape.n_rounds
+    series, _ = gen.signal_series(shape, 5)
+    print(f"controller series config={index} smoother={smoother} rounds={rounds}", flush=True)
+    ost = (np.zeros((shape.B, 3)), np.zeros(shape.B, np.int32), np.ones(shape.B, np.int32))
+    hist = O.new_histories(shape.B)
+    gst = gpu_state(shape.B, history=True)
+    ctx = gen.context_lengths(shape, 5)
+    n_exit = 0
+    for t in range(rounds):
+        case = gen.accept_case(shape, 3000 + t, p_split=0.3)
+        sig, ref = conditioned_round(kw, case, series[t], ctx, ost, hist)
+        got = gpu_accept_exit(kw, case.block_tok, None, case.target_argmax, sig, ctx, case.split_tok, gst)
+        compare(got, ref)
+        np.testing.assert_array_equal(host(gst[2]), ost[2])
+        np.testing.assert_allclose(host(gst[0]), ost[0], rtol=2e-5, atol=2e-5, err_msg=f"round {t}")
+        n_exit += int(ref["exit_flag"].sum())
+        ctx = ref["new_ctx_len"]
+    assert n_exit == shape.B, "every sequence should leave thinking within the series"
+    np.testing.assert_array_equal(host(gst[1]), ost[1])
+
+
+def test_smoothers_need_their_state_and_a_valid_window():
+    shape = gen.scaled(gen.config(1), B=2)
+    case = gen.accept_case(shape, 0)
+    sig = np.zeros((2, 3), np.float32)
+    ctx = np.array([5, 6], np.int32)
+    with pytest.raises(RuntimeError):
+        gpu_accept_exit(dict(smoother=2), case.block_tok, None, case.target_argmax, sig, ctx, case.split_tok, gpu_state(2))
+    with pytest.raises(RuntimeError):
+        gpu_accept_exit(dict(smoother=2, window=17), case.block_tok, None, case.target_argmax, sig, ctx,
+                        case.split_tok, gpu_state(2, history=True))
+    with pytest.raises(RuntimeError):
+        gpu_accept_exit(dict(smoother=5), case.block_tok, None, case.target_argmax, sig, ctx, case.split_tok,
+                        gpu_state(2, history=True))
+
+
 @pytest.mark.parametrize("index", [1, 4])
 def test_controller_over_many_rounds(index):
     """Whole signal series: exit round, lengths and state match the oracle at every round."""
