@@ -15,6 +15,10 @@ What is computed (SpecExit, arXiv 2509.24248):
                     through M_t with tree attention".
 * lmhead_argmax   - target logits -> next token per block position (greedy),
                     Alg. 1 "target model recover token".
+* kv_compact      - what the round leaves behind for the next one: the accepted
+                    path's K/V entries moved next to the context and the
+                    hidden state of the last accepted node, Alg. 1 "update
+                    KV-cache and hidden states accordingly".
 * accept_exit     - accepted tokens / accept length / recover token (Alg. 1),
                     EWMA smoothing (Sec. 3.3 "Signal Smoothing", Appendix
                     "Signal Smoothing" EWMA equation, alpha = 0.1; the sliding
@@ -450,3 +454,38 @@ def accept_exit(cfg: ExitCfg, block_tok, parent, target_argmax, sig, ctx_len, sp
         new_ctx[b] = int(ctx_len[b]) + 1 + len(path)
     return {"accept_len": accept_len, "accept_path": accept_path, "recover_tok": recover,
             "last_node": last_node, "exit_flag": exit_flag, "new_ctx_len": new_ctx}
+
+
+# ---------------------------------------------------------------------------
+# after the round: cache compaction  (Alg. 1, "update KV-cache and hidden states")
+# ---------------------------------------------------------------------------
+
+def kv_compact(k, v, ctx_len, accept_path, accept_len, page_table=None, page_size=16,
+               block_hidden=None, last_node=None):
+    """The cache as the next round must find it: the block root stays at position
+    L, the accepted node path[j] (stored at L + path[j] during verification)
+    becomes entry L + 1 + j, so that positions 0 .. L + accept_len hold exactly
+    the accepted sequence; whatever lies beyond is dead.  Every moved row is
+    read from the cache as it was before the call.  Returns new (k, v) arrays,
+    and with block_hidden [B, n_q, D] also the rows block_hidden[b, last_node[b]]
+    (the target's hidden state the next round's first draft step starts from)."""
+    k_new, v_new = np.array(k, copy=True), np.array(v, copy=True)
+    B = len(ctx_len)
+    Hkv = k.shape[1]
+
+    def row(b, head, pos):
+        if page_table is None:
+            return (b, head, pos)
+        return (int(page_table[b, pos // page_size]), head, pos % page_size)
+
+    for b in range(B):
+        L = int(ctx_len[b])
+        for j in range(int(accept_len[b])):
+            src, dst = L + int(accept_path[b, j]), L + 1 + j
+            for head in range(Hkv):
+                k_new[row(b, head, dst)] = k[row(b, head, src)]
+                v_new[row(b, head, dst)] = v[row(b, head, src)]
+    if block_hidden is None:
+        return k_new, v_new
+    hidden_next = np.stack([block_hidden[b, int(last_node[b])] for b in range(B)])
+    return k_new, v_new, hidden_next
