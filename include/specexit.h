@@ -201,6 +201,27 @@ int32_t specexit_accept_exit(const specexit_exit_cfg *cfg, int32_t B, int32_t n_
                              int32_t *exit_flag /*[B]*/, int32_t *new_ctx_len /*[B]*/,
                              uint32_t flags, void *stream);
 
+/* ---- after the round: cache compaction (Alg. 1, "update KV-cache and hidden states
+ * accordingly") ----
+ * Per sequence b, with L = ctx_len[b] (the value the round started with) and the outputs of
+ * specexit_accept_exit: the K/V entry of accepted node accept_path[b,j], stored at cache
+ * position L + accept_path[b,j] during verification, moves to position L + 1 + j for
+ * j < accept_len[b] (the root stays at L), in every one of the n_layers caches that lie
+ * layer_stride_bytes apart from kv->k / kv->v (all layers share kv's shape and, when
+ * paged, its page table).  Entries past L + accept_len[b] are dead afterwards; nothing
+ * else is written.  Every moved entry is read before any is written, so overlapping
+ * source and target positions are safe.  With block_hidden [B, n_q, D] (in kv->dtype, the
+ * target's final hidden states of the block) the row of last_node[b] is copied to
+ * hidden_next [B, D], the input of the next round's first draft step; block_hidden NULL
+ * skips that (last_node and hidden_next are then unused).  D * element size must be a
+ * multiple of 16.  A sequence whose block does not fit the cache (L + n_q > l_max) is left
+ * untouched. */
+int32_t specexit_kv_compact(const specexit_kv_view *kv, int32_t n_layers, int64_t layer_stride_bytes,
+                            int32_t B, int32_t n_q, const int32_t *ctx_len /*[B]*/,
+                            const int32_t *accept_path /*[B,n_q]*/, const int32_t *accept_len /*[B]*/,
+                            const int32_t *last_node /*[B]*/, const void *block_hidden /*[B,n_q,D] or NULL*/,
+                            int32_t D, void *hidden_next /*[B,D]*/, uint32_t flags, void *stream);
+
 /* ---- measurement aid -------------------------------------------------------------------
  * Hands the library n pairs of caller-owned hipEvent_t ([host] arrays of handles).  From then
  * on, each launch of the named kernel records the next unused pair around that one kernel on

@@ -24,7 +24,7 @@ EXPORTS = [
     "specexit_draft_step", "specexit_draft_step_workspace_bytes",
     "specexit_verify_attn", "specexit_verify_attn_workspace_bytes",
     "specexit_lmhead_argmax", "specexit_lmhead_argmax_workspace_bytes",
-    "specexit_accept_exit", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
+    "specexit_accept_exit", "specexit_kv_compact", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
 SMOOTH_EWMA, SMOOTH_NONE, SMOOTH_WINDOW, SMOOTH_MOMENTUM, SMOOTH_PARAGRAPH = 0, 1, 2, 3, 4
@@ -90,6 +90,8 @@ def _load() -> C.CDLL:
     lib.specexit_accept_exit.restype = i32
     lib.specexit_accept_exit.argtypes = [C.POINTER(ExitCfg), i32, i32, vp, vp, vp, vp, vp, vp, i32,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+    lib.specexit_kv_compact.restype = i32
+    lib.specexit_kv_compact.argtypes = [C.POINTER(KVView), i32, C.c_int64, i32, i32, vp, vp, vp, vp, vp, i32, vp, u32, vp]
     lib.specexit_copy_probe.restype = i32
     lib.specexit_copy_probe.argtypes = [vp, vp, sz, i32, vp]
     lib.specexit_profile_events.restype = i32
@@ -230,6 +232,14 @@ def specexit_accept_exit(cfg: ExitCfg, B: int, n_q: int, block_tok, parent, targ
                                     _ptr(sig), _ptr(ctx_len), _ptr(split_tok), S, _ptr(ewma), _ptr(n_obs),
                                     _ptr(is_thinking), _ptr(smooth_state), _ptr(accept_len), _ptr(accept_path), _ptr(recover_tok),
                                     _ptr(last_node), _ptr(exit_flag), _ptr(new_ctx_len), flags, _stream(stream)))
+
+
+def specexit_kv_compact(kv: KVView, n_layers: int, layer_stride_bytes: int, B: int, n_q: int, ctx_len, accept_path,
+                        accept_len, last_node=None, block_hidden=None, D: int = 0, hidden_next=None,
+                        flags: int = 0, stream=None) -> None:
+    _check(LIB.specexit_kv_compact(C.byref(kv), n_layers, layer_stride_bytes, B, n_q, _ptr(ctx_len), _ptr(accept_path),
+                                   _ptr(accept_len), _ptr(last_node), _ptr(block_hidden), D, _ptr(hidden_next),
+                                   flags, _stream(stream)))
 
 
 def specexit_profile_events(kernel: int, start_events=None, stop_events=None) -> int:

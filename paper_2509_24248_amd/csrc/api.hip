@@ -516,4 +516,39 @@ int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_
   return check_hip(launch_accept_exit(a, static_cast<hipStream_t>(stream)), "accept_exit");
 }
 
+int32_t specexit_kv_compact(const specexit_kv_view* kv, int32_t n_layers, int64_t layer_stride_bytes, int32_t B,
+                            int32_t n_q, const int32_t* ctx_len, const int32_t* accept_path,
+                            const int32_t* accept_len, const int32_t* last_node, const void* block_hidden,
+                            int32_t D, void* hidden_next, uint32_t flags, void* stream) {
+  (void)flags;
+  int32_t rc = check_kv(kv, "kv_compact");
+  if (rc) return rc;
+  if (B < 1) return fail(SPECEXIT_EINVAL, "kv_compact: B < 1");
+  if (n_q < 1 || n_q > SPECEXIT_MAX_NQ) return fail(SPECEXIT_EINVAL, "kv_compact: n_q %d outside 1..64", n_q);
+  if (n_layers < 1) return fail(SPECEXIT_EINVAL, "kv_compact: n_layers < 1");
+  if (n_layers > 1 && (layer_stride_bytes <= 0 || layer_stride_bytes % 16))
+    return fail(SPECEXIT_EINVAL, "kv_compact: layer stride must be a positive multiple of 16 bytes");
+  if (!ctx_len || !accept_path || !accept_len) return fail(SPECEXIT_EINVAL, "kv_compact: a required pointer is null");
+  CompactArgs a;
+  memset(&a, 0, sizeof(a));
+  a.paged = kv->layout == SPECEXIT_KV_PAGED;
+  a.k = kv->k; a.v = kv->v; a.page_table = kv->page_table;
+  a.page_size = a.paged ? kv->page_size : 16;
+  a.max_pages = kv->max_pages_per_seq;
+  a.l_max = a.paged ? static_cast<int64_t>(kv->max_pages_per_seq) * kv->page_size : kv->l_max;
+  a.layer_stride_bytes = n_layers > 1 ? layer_stride_bytes : 0;
+  a.n_layers = n_layers; a.B = B; a.n_q = n_q; a.Hkv = kv->n_kv_heads;
+  a.row_bytes = static_cast<int>(kv->head_dim * esize(kv->dtype));
+  a.ctx_len = ctx_len; a.accept_path = accept_path; a.accept_len = accept_len; a.last_node = last_node;
+  if (block_hidden) {
+    if (!last_node || !hidden_next) return fail(SPECEXIT_EINVAL, "kv_compact: block_hidden given without last_node / hidden_next");
+    if (D < 1 || (D * esize(kv->dtype)) % 16) return fail(SPECEXIT_EINVAL, "kv_compact: D * element size must be a multiple of 16");
+    a.block_hidden = block_hidden; a.hidden_next = hidden_next;
+    a.hidden_row_bytes = static_cast<int>(D * esize(kv->dtype));
+  }
+  if (!kv_compact_supported(a)) return fail(SPECEXIT_EUNSUPPORTED, "kv_compact: block of %d nodes with %d-byte rows", n_q, a.row_bytes);
+  if (kv->n_kv_heads > 65535 || B > 65535 || n_layers > 65535) return fail(SPECEXIT_EUNSUPPORTED, "kv_compact: grid too large");
+  return check_hip(launch_kv_compact(a, static_cast<hipStream_t>(stream)), "kv_compact");
+}
+
 }  // extern "C"

@@ -111,6 +111,24 @@ hipError_t launch_head_finalize(const DraftDims& dm, int B, const int32_t* argma
 // ---- measurement aid: copy of known size through the streaming load path -------------------
 hipError_t launch_copy_probe(const void* src, void* dst, size_t bytes, bool nontemporal, hipStream_t s);
 
+// ---- cache compaction after acceptance ---------------------------------------------------
+struct CompactArgs {
+  int paged;
+  void *k, *v;
+  const int32_t* page_table;
+  int page_size, max_pages;
+  int64_t l_max;
+  int64_t layer_stride_bytes;
+  int n_layers, B, n_q, Hkv;
+  int row_bytes;             // head_dim * element size
+  const int32_t *ctx_len, *accept_path, *accept_len, *last_node;
+  const void* block_hidden;  // [B][n_q][hidden_row_bytes] or nullptr
+  void* hidden_next;         // [B][hidden_row_bytes]
+  int hidden_row_bytes;
+};
+bool kv_compact_supported(const CompactArgs& a);
+hipError_t launch_kv_compact(const CompactArgs& a, hipStream_t s);
+
 // ---- controller ------------------------------------------------------------------------
 constexpr int kSmoothWords = 48;   // 3 signals x 16 words
 struct ExitArgs {
