@@ -10,6 +10,9 @@ What is computed (SpecExit, arXiv 2509.24248):
 * draft_step      - the draft ("MTP") forward whose output projection is widened
                     by three signal rows, Sec. 3.1 Eq. 1; signal activations as
                     used by the training losses, Sec. 3.2 Eqs. 3-5.
+* draft_tree      - the same forward run over a candidate tree of fixed topology
+                    (children = the parent's top-ranked tokens), producing the
+                    block that tree attention verifies, Alg. 1.
 * verify_attn     - the target's attention over [last accepted token | draft
                     candidates] with a tree (ancestor) mask, Alg. 1 "forward
                     through M_t with tree attention".
@@ -206,6 +209,56 @@ class DraftDims:
     rope_theta: float = 1e6
 
 
+def top_b_lowest(z: np.ndarray, b: int) -> np.ndarray:
+    """The b largest entries of z, largest first, lower index first among equals."""
+    z = np.asarray(z, dtype=F64)
+    order = sorted(range(len(z)), key=lambda i: (-z[i], i)) if len(z) <= 4096 else \
+        np.lexsort((np.arange(len(z)), -z))
+    return np.asarray(order[:b], dtype=np.int64)
+
+
+def _draft_row(dims: DraftDims, w: dict, k_cache, v_cache, b, tok, g, rope_pos, slot, visible,
+               page_table, page_size, store):
+    """The draft forward of one row of sequence b (steps 1-5 of draft_step): the
+    row's K/V are rotated for position rope_pos, stored in cache entry `slot`,
+    and its query attends to the cache entries listed in `visible` (which
+    include `slot`)."""
+    D, Hq, Hkv, d, V = dims.D, dims.Hq, dims.Hkv, dims.d, dims.V
+    G = Hq // Hkv
+    e = np.asarray(w["embed"][int(tok)], dtype=F64)
+    g = np.asarray(g, dtype=F64)
+    x = linear(np.concatenate([e, g])[None, :], w["w_fc"])[0]
+    n = rmsnorm(x, w["ln_attn"], dims.rms_eps)
+    qv = linear(n[None, :], w["w_q"])[0].reshape(Hq, d)
+    kv = linear(n[None, :], w["w_k"])[0].reshape(Hkv, d)
+    vv = linear(n[None, :], w["w_v"])[0].reshape(Hkv, d)
+    qv = rope_rotate_half(qv, rope_pos, dims.rope_theta)
+    kv = rope_rotate_half(kv, rope_pos, dims.rope_theta)
+    k_new = kv if store is None else store(kv)
+    v_new = vv if store is None else store(vv)
+    if page_table is None:
+        k_cache[b, :, slot, :] = k_new
+        v_cache[b, :, slot, :] = v_new
+    else:
+        pg = page_table[b, slot // page_size]
+        k_cache[pg, :, slot % page_size, :] = k_new
+        v_cache[pg, :, slot % page_size, :] = v_new
+    positions = np.asarray(visible, dtype=np.int64)
+    attn = np.empty(Hq * d, dtype=F64)
+    for h in range(Hq):
+        kk = _kv_rows(k_cache, page_table, page_size, b, h // G, positions)
+        vs = _kv_rows(v_cache, page_table, page_size, b, h // G, positions)
+        s = (kk @ qv[h]) / np.sqrt(d)
+        attn[h * d:(h + 1) * d] = softmax_two_pass(s) @ vs
+    a = x + linear(attn[None, :], w["w_o"])[0]
+    m = rmsnorm(a, w["ln_mlp"], dims.rms_eps)
+    act = silu(linear(m[None, :], w["w_gate"])[0]) * linear(m[None, :], w["w_up"])[0]
+    y = a + linear(act[None, :], w["w_down"])[0]
+    h_fin = rmsnorm(y, w["ln_final"], dims.rms_eps)
+    z = linear(h_fin[None, :], w["w_head"])[0]
+    return {"hidden_out": y, "h_final": h_fin, "logits": z[:V], "sig_raw": z[V:V + 3], "attn_out": attn}
+
+
 def draft_step(dims: DraftDims, w: dict, k_cache, v_cache, tok, hidden_in, pos,
                page_table=None, page_size=16, store=None):
     """One draft step for B rows (one per sequence).
@@ -226,8 +279,7 @@ def draft_step(dims: DraftDims, w: dict, k_cache, v_cache, tok, hidden_in, pos,
     verify_attn).  `store` optionally rounds what is written to the cache to the
     storage type (the GPU keeps the cache in that type)."""
     B = len(tok)
-    D, Hq, Hkv, d, V = dims.D, dims.Hq, dims.Hkv, dims.d, dims.V
-    G = Hq // Hkv
+    D, Hq, d, V = dims.D, dims.Hq, dims.d, dims.V
     hidden_out = np.empty((B, D), dtype=F64)
     logits = np.empty((B, V), dtype=F64)
     sig_raw = np.empty((B, 3), dtype=F64)
@@ -235,45 +287,76 @@ def draft_step(dims: DraftDims, w: dict, k_cache, v_cache, tok, hidden_in, pos,
     attn_out = np.empty((B, Hq * d), dtype=F64)
     h_final = np.empty((B, D), dtype=F64)
     for b in range(B):
-        e = np.asarray(w["embed"][int(tok[b])], dtype=F64)
-        g = np.asarray(hidden_in[b], dtype=F64)
-        x = linear(np.concatenate([e, g])[None, :], w["w_fc"])[0]
-        n = rmsnorm(x, w["ln_attn"], dims.rms_eps)
-        qv = linear(n[None, :], w["w_q"])[0].reshape(Hq, d)
-        kv = linear(n[None, :], w["w_k"])[0].reshape(Hkv, d)
-        vv = linear(n[None, :], w["w_v"])[0].reshape(Hkv, d)
         p = int(pos[b])
-        qv = rope_rotate_half(qv, p, dims.rope_theta)
-        kv = rope_rotate_half(kv, p, dims.rope_theta)
-        k_new = kv if store is None else store(kv)
-        v_new = vv if store is None else store(vv)
-        if page_table is None:
-            k_cache[b, :, p, :] = k_new
-            v_cache[b, :, p, :] = v_new
-        else:
-            pg = page_table[b, p // page_size]
-            k_cache[pg, :, p % page_size, :] = k_new
-            v_cache[pg, :, p % page_size, :] = v_new
-        positions = np.arange(p + 1, dtype=np.int64)
-        for h in range(Hq):
-            kk = _kv_rows(k_cache, page_table, page_size, b, h // G, positions)
-            vs = _kv_rows(v_cache, page_table, page_size, b, h // G, positions)
-            s = (kk @ qv[h]) / np.sqrt(d)
-            attn_out[b, h * d:(h + 1) * d] = softmax_two_pass(s) @ vs
-        a = x + linear(attn_out[b][None, :], w["w_o"])[0]
-        m = rmsnorm(a, w["ln_mlp"], dims.rms_eps)
-        act = silu(linear(m[None, :], w["w_gate"])[0]) * linear(m[None, :], w["w_up"])[0]
-        y = a + linear(act[None, :], w["w_down"])[0]
-        hidden_out[b] = y
-        h_fin = rmsnorm(y, w["ln_final"], dims.rms_eps)
-        h_final[b] = h_fin
-        z = linear(h_fin[None, :], w["w_head"])[0]
-        logits[b] = z[:V]
-        sig_raw[b] = z[V:V + 3]
-        next_tok[b] = argmax_lowest(z[:V])
+        r = _draft_row(dims, w, k_cache, v_cache, b, tok[b], hidden_in[b], p, p, np.arange(p + 1),
+                       page_table, page_size, store)
+        hidden_out[b], h_final[b], logits[b] = r["hidden_out"], r["h_final"], r["logits"]
+        sig_raw[b], attn_out[b] = r["sig_raw"], r["attn_out"]
+        next_tok[b] = argmax_lowest(r["logits"])
     return {"hidden_out": hidden_out, "next_tok": next_tok, "sig_raw": sig_raw,
             "sig": signal_activations(sig_raw), "logits": logits, "attn_out": attn_out,
             "h_final": h_final}
+
+
+def tree_depths(parent) -> np.ndarray:
+    depth = np.zeros(len(parent), dtype=np.int64)
+    for c in range(1, len(parent)):
+        depth[c] = depth[int(parent[c])] + 1
+    return depth
+
+
+def draft_tree(dims: DraftDims, w: dict, k_cache, v_cache, tok0, g0, ctx_len, parent, rank,
+               page_table=None, page_size=16, store=None):
+    """Draft a whole candidate tree of fixed topology for every sequence (the
+    block that verification with tree attention consumes, Alg. 1).
+
+    parent[c] < c is the parent of node c (node 0 = the last accepted token,
+    parent -1), rank[c] says which of the parent's continuations node c holds:
+    its token is the rank[c]-th most likely token (0 = argmax) of the draft's
+    output at the parent.  Every node that has children is run through the
+    draft forward (the row of draft_step): its inputs are its token and the
+    hidden state its parent's forward produced (node 0: the target's hidden
+    state g0), its rotary position is L + depth, its K/V go to draft cache
+    entry L + node, and it attends to the context 0..L-1 plus the entries of
+    its ancestors and itself.  Hidden states are handed from parent to child in
+    the storage type (`store`).  Nodes are processed in index order, which is a
+    topological order.
+
+    Returns block_tok [B, n], hidden_out / h_final / logits / sig_raw / sig per
+    expanded node (NaN rows elsewhere), and `expanded` [n] bool."""
+    n = len(parent)
+    B = len(tok0)
+    depth = tree_depths(parent)
+    children = [[c for c in range(1, n) if int(parent[c]) == p] for p in range(n)]
+    expanded = np.array([len(ch) > 0 for ch in children])
+    block_tok = np.zeros((B, n), dtype=np.int64)
+    hidden_out = np.full((B, n, dims.D), np.nan, dtype=F64)
+    h_final = np.full((B, n, dims.D), np.nan, dtype=F64)
+    logits = np.full((B, n, dims.V), np.nan, dtype=F64)
+    sig_raw = np.full((B, n, 3), np.nan, dtype=F64)
+    keep = (lambda a: a) if store is None else store
+    for b in range(B):
+        L = int(ctx_len[b])
+        block_tok[b, 0] = int(tok0[b])
+        for c in range(n):
+            if c > 0:
+                p = int(parent[c])
+                need = max(int(rank[k]) for k in children[p]) + 1
+                block_tok[b, c] = int(top_b_lowest(logits[b, p], need)[int(rank[c])])
+            if not expanded[c]:
+                continue
+            g = g0[b] if c == 0 else keep(hidden_out[b, int(parent[c])])
+            anc, a = [], c
+            while a >= 0:
+                anc.append(a)
+                a = int(parent[a])
+            visible = list(range(L)) + [L + a for a in sorted(anc)]
+            r = _draft_row(dims, w, k_cache, v_cache, b, block_tok[b, c], g, L + int(depth[c]), L + c,
+                           visible, page_table, page_size, store)
+            hidden_out[b, c], h_final[b, c], logits[b, c] = r["hidden_out"], r["h_final"], r["logits"]
+            sig_raw[b, c] = r["sig_raw"]
+    return {"block_tok": block_tok, "hidden_out": hidden_out, "h_final": h_final, "logits": logits,
+            "sig_raw": sig_raw, "sig": signal_activations(sig_raw), "expanded": expanded}
 
 
 # ---------------------------------------------------------------------------
