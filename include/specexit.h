@@ -48,6 +48,7 @@ typedef enum { SPECEXIT_KV_CONTIG = 0, SPECEXIT_KV_PAGED = 1 } specexit_kv_layou
  * n_q_heads % n_kv_heads == 0; (n_q_heads / n_kv_heads) * n_q <= 128;
  * page_size a multiple of 16; hidden, intermediate, n_q_heads*head_dim multiples of 64. */
 #define SPECEXIT_MAX_NQ 64
+#define SPECEXIT_MAX_TOP_B 4 /* ranked continuations a tree-drafting row can report */
 #define SPECEXIT_N_SIGNALS 3
 
 /* Draft model dimensions (the draft layer mirrors the target's attention geometry). */
@@ -138,6 +139,48 @@ int32_t specexit_draft_step(const specexit_model_desc *desc, const specexit_draf
                             void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 size_t specexit_draft_step_workspace_bytes(const specexit_model_desc *desc,
                                            const specexit_kv_view *draft_kv, int32_t B);
+
+/* ---- stage 1 over a tree: one level of tree drafting (the block "forward through M_t with
+ * tree attention" of Alg. 1 verifies; the draft forward is that of specexit_draft_step) ----
+ * The candidate tree has a fixed topology: node 0 is the last accepted token, node c > 0 holds
+ * the rank[c]-th most likely continuation (0 = argmax) of its parent.  A level call runs the
+ * draft forward for W nodes of equal depth `level` of each of the B sequences (rows ordered
+ * [B, W]; B * W <= 64): row (b, w) has token tok[b,w], input hidden state hidden_in[b,w,:] (its
+ * parent's hidden_out; the target's hidden state for node 0), rotary position ctx_len[b] + level,
+ * its K/V are stored in draft cache entry ctx_len[b] + node[w], and it attends to the context
+ * 0..ctx_len[b]-1 plus the block entries ctx_len[b] + j whose bit j is set in anc_mask[w]
+ * (ancestors and itself; node and anc_mask are device arrays shared by all sequences).
+ * Entries ctx_len[b] .. ctx_len[b] + n_blk - 1 must hold finite values once this call has
+ * written its own (number the nodes level by level and pass n_blk = last node of this level
+ * + 1).  Outputs per row: hidden_out, the top_b best tokens cand_tok[b,w,0:top_b] (logit
+ * descending, lower index first among equals) with their logits cand_logit (may be NULL),
+ * sig_raw and sig as in specexit_draft_step.  With W = 1, level = 0, node = {0}, anc_mask =
+ * {1}, n_blk = 1, top_b = 1 this is specexit_draft_step at pos = ctx_len. */
+int32_t specexit_draft_tree_level(const specexit_model_desc *desc, const specexit_draft_weights *w,
+                                  const specexit_kv_view *draft_kv, int32_t B, int32_t W,
+                                  const int32_t *tok /*[B,W]*/, const void *hidden_in /*[B,W,D]*/,
+                                  const int32_t *ctx_len /*[B]*/, int32_t level,
+                                  const int32_t *node /*[W]*/, const uint64_t *anc_mask /*[W]*/,
+                                  int32_t n_blk, int32_t top_b,
+                                  void *hidden_out /*[B,W,D]*/, int32_t *cand_tok /*[B,W,top_b]*/,
+                                  float *cand_logit /*[B,W,top_b] or NULL*/,
+                                  float *sig_raw /*[B,W,3]*/, float *sig /*[B,W,3]*/,
+                                  void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
+size_t specexit_draft_tree_level_workspace_bytes(const specexit_model_desc *desc,
+                                                 const specexit_kv_view *draft_kv, int32_t B,
+                                                 int32_t W, int32_t top_b);
+
+/* Between two levels: row wn of the next level is the child with rank rank[wn] of row
+ * src_row[wn] of the level just computed: tok_next[b,wn] = cand_tok[b, src_row[wn], rank[wn]]
+ * (also written to block_tok[b, node[wn]] when block_tok [B, n_q] is given) and
+ * hidden_next[b,wn,:] = hidden_prev[b, src_row[wn], :] (skipped when hidden_next is NULL: leaves
+ * need no forward).  src_row, rank, node are device arrays [W_next]. */
+int32_t specexit_tree_gather(int32_t dtype, int32_t B, int32_t W_prev, int32_t top_b, int32_t W_next,
+                             int32_t D, int32_t n_q, const int32_t *src_row, const int32_t *rank,
+                             const int32_t *node, const int32_t *cand_tok /*[B,W_prev,top_b]*/,
+                             const void *hidden_prev /*[B,W_prev,D]*/, int32_t *tok_next /*[B,W_next]*/,
+                             void *hidden_next /*[B,W_next,D] or NULL*/, int32_t *block_tok /*[B,n_q] or NULL*/,
+                             uint32_t flags, void *stream);
 
 /* ---- stage 2: verification attention (Alg. 1, "forward through M_t with tree attention") ----
  * out[b,i,h,:] = sum_j softmax_j(scale * q[b,i,h,:] . K[j]) V[j] over the visible cache

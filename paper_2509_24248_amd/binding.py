@@ -24,6 +24,7 @@ EXPORTS = [
     "specexit_draft_step", "specexit_draft_step_workspace_bytes",
     "specexit_verify_attn", "specexit_verify_attn_workspace_bytes",
     "specexit_lmhead_argmax", "specexit_lmhead_argmax_workspace_bytes",
+    "specexit_draft_tree_level", "specexit_draft_tree_level_workspace_bytes", "specexit_tree_gather",
     "specexit_accept_exit", "specexit_kv_compact", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
@@ -90,6 +91,13 @@ def _load() -> C.CDLL:
     lib.specexit_accept_exit.restype = i32
     lib.specexit_accept_exit.argtypes = [C.POINTER(ExitCfg), i32, i32, vp, vp, vp, vp, vp, vp, i32,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+    lib.specexit_draft_tree_level_workspace_bytes.restype = sz
+    lib.specexit_draft_tree_level_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(KVView), i32, i32, i32]
+    lib.specexit_draft_tree_level.restype = i32
+    lib.specexit_draft_tree_level.argtypes = [C.POINTER(ModelDesc), C.POINTER(DraftWeights), C.POINTER(KVView), i32, i32,
+                                              vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, u32, vp]
+    lib.specexit_tree_gather.restype = i32
+    lib.specexit_tree_gather.argtypes = [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
     lib.specexit_kv_compact.restype = i32
     lib.specexit_kv_compact.argtypes = [C.POINTER(KVView), i32, C.c_int64, i32, i32, vp, vp, vp, vp, vp, i32, vp, u32, vp]
     lib.specexit_copy_probe.restype = i32
@@ -200,6 +208,28 @@ def specexit_draft_step(desc: ModelDesc, w: DraftWeights, draft_kv: KVView, B: i
     _check(LIB.specexit_draft_step(C.byref(desc), C.byref(w), C.byref(draft_kv), B, _ptr(tok), _ptr(hidden_in),
                                    _ptr(pos), _ptr(hidden_out), _ptr(next_tok), _ptr(sig_raw), _ptr(sig),
                                    wp, wb, flags, _stream(stream)))
+
+
+def specexit_draft_tree_level_workspace_bytes(desc: ModelDesc, draft_kv: KVView, B: int, W: int, top_b: int) -> int:
+    return int(LIB.specexit_draft_tree_level_workspace_bytes(C.byref(desc), C.byref(draft_kv), B, W, top_b))
+
+
+def specexit_draft_tree_level(desc: ModelDesc, w: DraftWeights, draft_kv: KVView, B: int, W: int, tok, hidden_in,
+                              ctx_len, level: int, node, anc_mask, n_blk: int, top_b: int, hidden_out, cand_tok,
+                              cand_logit, sig_raw, sig, workspace, flags: int = 0, stream=None) -> None:
+    wp, wb = _ws_args(workspace)
+    _check(LIB.specexit_draft_tree_level(C.byref(desc), C.byref(w), C.byref(draft_kv), B, W, _ptr(tok), _ptr(hidden_in),
+                                         _ptr(ctx_len), level, _ptr(node), _ptr(anc_mask), n_blk, top_b,
+                                         _ptr(hidden_out), _ptr(cand_tok), _ptr(cand_logit), _ptr(sig_raw), _ptr(sig),
+                                         wp, wb, flags, _stream(stream)))
+
+
+def specexit_tree_gather(dtype: int, B: int, W_prev: int, top_b: int, W_next: int, D: int, n_q: int, src_row, rank,
+                         node, cand_tok, hidden_prev, tok_next, hidden_next=None, block_tok=None, flags: int = 0,
+                         stream=None) -> None:
+    _check(LIB.specexit_tree_gather(dtype, B, W_prev, top_b, W_next, D, n_q, _ptr(src_row), _ptr(rank), _ptr(node),
+                                    _ptr(cand_tok), _ptr(hidden_prev), _ptr(tok_next), _ptr(hidden_next),
+                                    _ptr(block_tok), flags, _stream(stream)))
 
 
 def specexit_verify_attn_workspace_bytes(kv: KVView, B: int, n_q: int, n_q_heads: int) -> int:

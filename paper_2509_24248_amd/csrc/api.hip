@@ -126,6 +126,8 @@ int32_t fill_attn(AttnArgs& a, const specexit_kv_view* kv, int32_t B, int32_t n_
   a.l_max = a.paged ? static_cast<int64_t>(kv->max_pages_per_seq) * kv->page_size : kv->l_max;
   a.B = B;
   a.n_q = n_q;
+  a.n_blk = n_q;
+  a.mask_stride = n_q;
   a.Hq = n_q_heads;
   a.Hkv = kv->n_kv_heads;
   a.d = kv->head_dim;
@@ -137,7 +139,9 @@ int32_t fill_attn(AttnArgs& a, const specexit_kv_view* kv, int32_t B, int32_t n_
 struct DraftPlan {
   DraftDims dm;
   bool mfma;
-  int B;
+  int B;        // rows of the step: sequences x rows per sequence
+  int nseq, W;  // sequences, rows (tree nodes of one level) per sequence
+  int top_b;    // continuations reported per row
   int Kmax;
   GemmArgs fc, qkv, o, gu, down, head;
   AttnArgs attn;
@@ -162,15 +166,18 @@ size_t partial_bytes_of(const GemmArgs& g, bool mfma) {
   return static_cast<size_t>(g.ksplit) * g.M * g.planes * g.N * sizeof(float);
 }
 
-int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specexit_kv_view* kv, int32_t B) {
+int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specexit_kv_view* kv, int32_t nseq,
+                        int32_t W = 1, int32_t top_b = 1) {
+  const int32_t B = nseq * W;
   if (!d || d->struct_size != sizeof(specexit_model_desc)) return fail(SPECEXIT_EINVAL, "draft_step: model desc missing or of another ABI size");
   if (!dtype_ok(d->dtype)) return fail(SPECEXIT_EINVAL, "draft_step: unknown dtype %d", d->dtype);
-  if (B < 1 || B > 64) return fail(SPECEXIT_EINVAL, "draft_step: B %d outside 1..64", B);
+  if (nseq < 1 || W < 1 || B > 64) return fail(SPECEXIT_EINVAL, "draft_step: %d sequences x %d rows outside 1..64 rows", nseq, W);
+  if (top_b < 1 || top_b > SPECEXIT_MAX_TOP_B) return fail(SPECEXIT_EINVAL, "draft_step: top_b %d outside 1..%d", top_b, SPECEXIT_MAX_TOP_B);
   if (d->hidden < 64 || d->hidden % 64 || d->hidden > 8192) return fail(SPECEXIT_EUNSUPPORTED, "draft_step: hidden %d must be a multiple of 64 up to 8192", d->hidden);
   if (d->intermediate < 64 || d->intermediate % 64) return fail(SPECEXIT_EUNSUPPORTED, "draft_step: intermediate %d must be a multiple of 64", d->intermediate);
   if (d->vocab < 1) return fail(SPECEXIT_EINVAL, "draft_step: vocab < 1");
   if (d->rem_activation < 0 || d->rem_activation > 2) return fail(SPECEXIT_EINVAL, "draft_step: rem_activation %d", d->rem_activation);
-  int32_t rc = fill_attn(p.attn, kv, B, 1, d->n_q_heads, "draft_step");
+  int32_t rc = fill_attn(p.attn, kv, nseq, W, d->n_q_heads, "draft_step");
   if (rc) return rc;
   if (kv->dtype != d->dtype || kv->n_kv_heads != d->n_kv_heads || kv->head_dim != d->head_dim)
     return fail(SPECEXIT_EINVAL, "draft_step: draft kv view does not match the model desc");
@@ -179,6 +186,9 @@ int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specex
   dm.I = d->intermediate; dm.V = d->vocab; dm.rms_eps = d->rms_eps; dm.rope_theta = d->rope_theta;
   dm.rem_activation = d->rem_activation;
   p.B = B;
+  p.nseq = nseq;
+  p.W = W;
+  p.top_b = top_b;
   const int D = dm.D, Hd = dm.Hq * dm.d, I = dm.I;
   p.Kmax = 2 * D > Hd ? 2 * D : Hd;
   if (I > p.Kmax) p.Kmax = I;
@@ -198,6 +208,7 @@ int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specex
   plan_gemm(p.down, D, I, B, 2, p.mfma, -1);
   plan_gemm(p.head, dm.V + 3, D, B, 2, p.mfma, dm.V);
   p.head.n_extra = 3;
+  p.head.top_b = top_b;
   p.ntiles_head = gemm_ntiles(dm.V + 3);
   size_t pb = 0;
   const GemmArgs* all[6] = {&p.fc, &p.qkv, &p.o, &p.gu, &p.down, &p.head};
@@ -233,8 +244,8 @@ DraftBufs carve_draft(const DraftPlan& p, void* ws) {
   b.q_buf = c.take<char>(es * p.B * p.dm.Hq * p.dm.d);
   b.attn_out = c.take<char>(es * p.B * p.dm.Hq * p.dm.d);
   b.attn_ws = c.take<char>(attn_workspace_bytes(p.attn));
-  b.part_val = c.take<float>(sizeof(float) * p.B * p.ntiles_head);
-  b.part_idx = c.take<int>(sizeof(int) * p.B * p.ntiles_head);
+  b.part_val = c.take<float>(sizeof(float) * p.B * p.ntiles_head * p.top_b);
+  b.part_idx = c.take<int>(sizeof(int) * p.B * p.ntiles_head * p.top_b);
   b.head_am = c.take<int32_t>(sizeof(int32_t) * p.B);
   b.extra = c.take<float>(sizeof(float) * p.B * 3);
   b.total = c.off;
@@ -251,6 +262,108 @@ int32_t run_gemm(GemmArgs g, bool mfma, bool bf16, const void* w0, const void* w
   g.part_idx = b.part_idx;
   g.extra_out = b.extra;
   return check_hip(mfma ? launch_gemm_mfma(g, s) : launch_gemm_valu(g, bf16, s), what);
+}
+
+// Inputs and outputs of one draft forward over p.B = nseq * W rows (row r = sequence r / W).
+struct DraftIO {
+  const int32_t* tok;        // [rows]
+  const void* hidden_in;     // [rows, D]
+  const int32_t* pos;        // [nseq] cache entries before this step's block
+  int level;                 // rotary position = pos + level
+  const int32_t* node;       // [W] cache entry = pos + node (null: pos itself)
+  const uint64_t* mask;      // [W] visible block entries per row, shared by the sequences (null: chain)
+  int n_blk;                 // block entries that exist after the context
+  void* hidden_out;          // [rows, D]
+  int32_t* cand_tok;         // [rows, top_b]
+  float* cand_logit;         // [rows, top_b] or null
+  float *sig_raw, *sig;      // [rows, 3]
+};
+
+int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_kv_view* draft_kv, const DraftIO& io,
+                  void* workspace, size_t workspace_bytes, hipStream_t s) {
+  int32_t rc;
+  const int B = p.B;   // rows
+  if (!w || w->struct_size != sizeof(specexit_draft_weights)) return fail(SPECEXIT_EINVAL, "draft_step: weights missing or of another ABI size");
+  const void* ptrs[] = {w->embed, w->w_fc, w->ln_attn, w->ln_mlp, w->ln_final, w->w_q, w->w_k, w->w_v,
+                        w->w_o, w->w_gate, w->w_up, w->w_down, w->w_head, io.tok, io.hidden_in, io.pos, io.hidden_out,
+                        io.cand_tok, io.sig_raw, io.sig};
+  for (const void* q : ptrs)
+    if (!q) return fail(SPECEXIT_EINVAL, "draft_step: a required pointer is null");
+  if (io.hidden_in == io.hidden_out) return fail(SPECEXIT_EINVAL, "draft_step: hidden_in and hidden_out alias");
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return fail(SPECEXIT_EWORKSPACE, "draft_step: workspace null or not 256-byte aligned");
+  const DraftBufs b = carve_draft(p, workspace);
+  if (workspace_bytes < b.total) return fail(SPECEXIT_EWORKSPACE, "draft_step: workspace %zu < %zu bytes", workspace_bytes, b.total);
+  const DraftDims& dm = p.dm;
+  const bool bf16 = dm.dtype == SPECEXIT_BF16;
+  const bool mf = p.mfma;
+
+  // x = W_fc [embed[tok] ; hidden_in]
+  if (mf) {
+    p.fc.a_mode = 2;   // the GEMM gathers [embed[tok] ; hidden_in] itself
+    p.fc.a_src = io.hidden_in;
+    p.fc.a_embed = w->embed;
+    p.fc.a_tok = io.tok;
+  } else {
+    if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, io.tok, io.hidden_in, b.act, s), "embed_concat"))) return rc;
+  }
+  if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
+  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.fc.ksplit, p.fc.planes, nullptr, w->ln_attn,
+                                         b.x_buf, nullptr, b.act, s), "norm attn"))) return rc;
+  // q, k, v; rotary; cache write; attention over the draft's own cache
+  if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
+  if ((rc = check_hip(launch_rope_kvwrite(dm, B, p.W, b.partial, p.qkv.ksplit, p.qkv.planes, io.pos, io.level, io.node,
+                                          b.q_buf, p.attn.paged, draft_kv->k, draft_kv->v, draft_kv->page_table,
+                                          p.attn.page_size, p.attn.max_pages, p.attn.l_max, s), "rope"))) return rc;
+  AttnArgs at = p.attn;
+  at.q = b.q_buf;
+  at.ctx_len = io.pos;
+  at.mask = io.mask;
+  at.mask_stride = 0;
+  at.n_blk = io.n_blk;
+  at.scale = 1.0f / sqrtf(static_cast<float>(dm.d));
+  at.out = b.attn_out;
+  {
+    Carver c(b.attn_ws);
+    const size_t R = static_cast<size_t>(at.Hq / at.Hkv) * at.n_q;
+    const size_t units = static_cast<size_t>(at.B) * at.Hkv * at.nsplit;
+    at.part_o = c.take<float>(units * R * at.d * sizeof(float));
+    at.part_ml = c.take<float>(units * R * 2 * sizeof(float));
+  }
+  if ((rc = check_hip(launch_attn(at, s, &g_prof_hook, SPECEXIT_PROF_DRAFT_ATTN), "draft attention"))) return rc;
+  // a = x + W_o attn
+  if (mf) {
+    p.o.a_mode = 1;    // attention output is read in its storage type
+    p.o.a_src = b.attn_out;
+  } else {
+    if ((rc = check_hip(launch_unpack_rows(b.attn_out, bf16, B, dm.Hq * dm.d, b.act, s), "unpack attn"))) return rc;
+  }
+  if ((rc = run_gemm(p.o, mf, bf16, w->w_o, nullptr, nullptr, b, s, "gemm o"))) return rc;
+  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.o.ksplit, p.o.planes, b.x_buf, w->ln_mlp,
+                                         b.a_buf, nullptr, b.act, s), "norm mlp"))) return rc;
+  // y = a + W_down (silu(W_gate m) * W_up m)
+  if ((rc = run_gemm(p.gu, mf, bf16, w->w_gate, w->w_up, nullptr, b, s, "gemm gate/up"))) return rc;
+  if ((rc = check_hip(launch_silu_mul(dm, B, b.partial, p.gu.ksplit, p.gu.planes, b.act, s), "silu"))) return rc;
+  if ((rc = run_gemm(p.down, mf, bf16, w->w_down, nullptr, nullptr, b, s, "gemm down"))) return rc;
+  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.down.ksplit, p.down.planes, b.a_buf, w->ln_final,
+                                         nullptr, io.hidden_out, b.act, s), "norm final"))) return rc;
+  // widened head (Eq. 1): argmax (or the top_b best) over the vocabulary rows, three signal rows on the side
+  {
+    ProfScope prof(SPECEXIT_PROF_DRAFT_HEAD_GEMM, s);
+    if ((rc = run_gemm(p.head, mf, bf16, w->w_head, nullptr, nullptr, b, s, "gemm head"))) return rc;
+  }
+  if (mf) {
+    if (p.top_b == 1 && !io.cand_logit)
+      return check_hip(launch_argmax_finalize(b.part_val, b.part_idx, p.ntiles_head, B, io.cand_tok, nullptr, s, b.extra,
+                                              dm.rem_activation, io.sig_raw, io.sig), "argmax finalize");
+    const int C = p.ntiles_head * p.top_b;
+    return check_hip(launch_topb_finalize(b.part_val, b.part_idx, C, C, p.top_b, B, io.cand_tok, io.cand_logit, s,
+                                          b.extra, dm.rem_activation, io.sig_raw, io.sig), "top-b finalize");
+  }
+  if ((rc = check_hip(launch_argmax_rows(b.partial, B, dm.V + 3, dm.V, 3, b.head_am, nullptr, b.extra, nullptr, s), "argmax rows"))) return rc;
+  if (p.top_b == 1 && !io.cand_logit)
+    return check_hip(launch_head_finalize(dm, B, b.head_am, b.extra, io.cand_tok, io.sig_raw, io.sig, s), "head finalize");
+  return check_hip(launch_topb_finalize(b.partial, nullptr, dm.V, dm.V + 3, p.top_b, B, io.cand_tok, io.cand_logit, s,
+                                        b.extra, dm.rem_activation, io.sig_raw, io.sig), "top-b rows");
 }
 
 }  // namespace
@@ -296,78 +409,40 @@ int32_t specexit_draft_step(const specexit_model_desc* desc, const specexit_draf
   DraftPlan p;
   int32_t rc = make_draft_plan(p, desc, draft_kv, B);
   if (rc) return rc;
-  if (!w || w->struct_size != sizeof(specexit_draft_weights)) return fail(SPECEXIT_EINVAL, "draft_step: weights missing or of another ABI size");
-  const void* ptrs[] = {w->embed, w->w_fc, w->ln_attn, w->ln_mlp, w->ln_final, w->w_q, w->w_k, w->w_v,
-                        w->w_o, w->w_gate, w->w_up, w->w_down, w->w_head, tok, hidden_in, pos, hidden_out,
-                        next_tok, sig_raw, sig};
-  for (const void* q : ptrs)
-    if (!q) return fail(SPECEXIT_EINVAL, "draft_step: a required pointer is null");
-  if (hidden_in == hidden_out) return fail(SPECEXIT_EINVAL, "draft_step: hidden_in and hidden_out alias");
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return fail(SPECEXIT_EWORKSPACE, "draft_step: workspace null or not 256-byte aligned");
-  const DraftBufs b = carve_draft(p, workspace);
-  if (workspace_bytes < b.total) return fail(SPECEXIT_EWORKSPACE, "draft_step: workspace %zu < %zu bytes", workspace_bytes, b.total);
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  const DraftDims& dm = p.dm;
-  const bool bf16 = dm.dtype == SPECEXIT_BF16;
-  const bool mf = p.mfma;
+  DraftIO io;
+  memset(&io, 0, sizeof(io));
+  io.tok = tok; io.hidden_in = hidden_in; io.pos = pos; io.n_blk = 1;
+  io.hidden_out = hidden_out; io.cand_tok = next_tok; io.sig_raw = sig_raw; io.sig = sig;
+  return run_draft(p, w, draft_kv, io, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
+}
 
-  // x = W_fc [embed[tok] ; hidden_in]
-  if (mf) {
-    p.fc.a_mode = 2;   // the GEMM gathers [embed[tok] ; hidden_in] itself
-    p.fc.a_src = hidden_in;
-    p.fc.a_embed = w->embed;
-    p.fc.a_tok = tok;
-  } else {
-    if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, tok, hidden_in, b.act, s), "embed_concat"))) return rc;
-  }
-  if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
-  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.fc.ksplit, p.fc.planes, nullptr, w->ln_attn,
-                                         b.x_buf, nullptr, b.act, s), "norm attn"))) return rc;
-  // q, k, v; rotary; cache write; attention over the draft's own cache
-  if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
-  if ((rc = check_hip(launch_rope_kvwrite(dm, B, b.partial, p.qkv.ksplit, p.qkv.planes, pos, b.q_buf, p.attn.paged,
-                                          draft_kv->k, draft_kv->v, draft_kv->page_table, p.attn.page_size,
-                                          p.attn.max_pages, p.attn.l_max, s), "rope"))) return rc;
-  AttnArgs at = p.attn;
-  at.q = b.q_buf;
-  at.ctx_len = pos;
-  at.mask = nullptr;
-  at.scale = 1.0f / sqrtf(static_cast<float>(dm.d));
-  at.out = b.attn_out;
-  {
-    Carver c(b.attn_ws);
-    const size_t R = static_cast<size_t>(at.Hq / at.Hkv) * at.n_q;
-    const size_t units = static_cast<size_t>(at.B) * at.Hkv * at.nsplit;
-    at.part_o = c.take<float>(units * R * at.d * sizeof(float));
-    at.part_ml = c.take<float>(units * R * 2 * sizeof(float));
-  }
-  if ((rc = check_hip(launch_attn(at, s, &g_prof_hook, SPECEXIT_PROF_DRAFT_ATTN), "draft attention"))) return rc;
-  // a = x + W_o attn
-  if (mf) {
-    p.o.a_mode = 1;    // attention output is read in its storage type
-    p.o.a_src = b.attn_out;
-  } else {
-    if ((rc = check_hip(launch_unpack_rows(b.attn_out, bf16, B, dm.Hq * dm.d, b.act, s), "unpack attn"))) return rc;
-  }
-  if ((rc = run_gemm(p.o, mf, bf16, w->w_o, nullptr, nullptr, b, s, "gemm o"))) return rc;
-  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.o.ksplit, p.o.planes, b.x_buf, w->ln_mlp,
-                                         b.a_buf, nullptr, b.act, s), "norm mlp"))) return rc;
-  // y = a + W_down (silu(W_gate m) * W_up m)
-  if ((rc = run_gemm(p.gu, mf, bf16, w->w_gate, w->w_up, nullptr, b, s, "gemm gate/up"))) return rc;
-  if ((rc = check_hip(launch_silu_mul(dm, B, b.partial, p.gu.ksplit, p.gu.planes, b.act, s), "silu"))) return rc;
-  if ((rc = run_gemm(p.down, mf, bf16, w->w_down, nullptr, nullptr, b, s, "gemm down"))) return rc;
-  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.down.ksplit, p.down.planes, b.a_buf, w->ln_final,
-                                         nullptr, hidden_out, b.act, s), "norm final"))) return rc;
-  // widened head (Eq. 1): argmax over the vocabulary rows, three signal rows on the side
-  {
-    ProfScope prof(SPECEXIT_PROF_DRAFT_HEAD_GEMM, s);
-    if ((rc = run_gemm(p.head, mf, bf16, w->w_head, nullptr, nullptr, b, s, "gemm head"))) return rc;
-  }
-  if (mf)
-    return check_hip(launch_argmax_finalize(b.part_val, b.part_idx, p.ntiles_head, B, next_tok, nullptr, s, b.extra,
-                                            dm.rem_activation, sig_raw, sig), "argmax finalize");
-  if ((rc = check_hip(launch_argmax_rows(b.partial, B, dm.V + 3, dm.V, 3, b.head_am, nullptr, b.extra, nullptr, s), "argmax rows"))) return rc;
-  return check_hip(launch_head_finalize(dm, B, b.head_am, b.extra, next_tok, sig_raw, sig, s), "head finalize");
+size_t specexit_draft_tree_level_workspace_bytes(const specexit_model_desc* desc, const specexit_kv_view* draft_kv,
+                                                 int32_t B, int32_t W, int32_t top_b) {
+  DraftPlan p;
+  if (make_draft_plan(p, desc, draft_kv, B, W, top_b)) return 0;
+  return carve_draft(p, nullptr).total;
+}
+
+int32_t specexit_draft_tree_level(const specexit_model_desc* desc, const specexit_draft_weights* w,
+                                  const specexit_kv_view* draft_kv, int32_t B, int32_t W, const int32_t* tok,
+                                  const void* hidden_in, const int32_t* ctx_len, int32_t level,
+                                  const int32_t* node, const uint64_t* anc_mask, int32_t n_blk, int32_t top_b,
+                                  void* hidden_out, int32_t* cand_tok, float* cand_logit, float* sig_raw,
+                                  float* sig, void* workspace, size_t workspace_bytes, uint32_t flags,
+                                  void* stream) {
+  (void)flags;
+  DraftPlan p;
+  int32_t rc = make_draft_plan(p, desc, draft_kv, B, W, top_b);
+  if (rc) return rc;
+  if (level < 0) return fail(SPECEXIT_EINVAL, "draft_tree_level: level < 0");
+  if (n_blk < 1 || n_blk > SPECEXIT_MAX_NQ) return fail(SPECEXIT_EINVAL, "draft_tree_level: n_blk %d outside 1..64", n_blk);
+  if (!node || !anc_mask) return fail(SPECEXIT_EINVAL, "draft_tree_level: node ids or ancestor masks missing");
+  DraftIO io;
+  memset(&io, 0, sizeof(io));
+  io.tok = tok; io.hidden_in = hidden_in; io.pos = ctx_len; io.level = level; io.node = node;
+  io.mask = anc_mask; io.n_blk = n_blk;
+  io.hidden_out = hidden_out; io.cand_tok = cand_tok; io.cand_logit = cand_logit; io.sig_raw = sig_raw; io.sig = sig;
+  return run_draft(p, w, draft_kv, io, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 size_t specexit_verify_attn_workspace_bytes(const specexit_kv_view* kv, int32_t B, int32_t n_q, int32_t n_q_heads) {
@@ -514,6 +589,31 @@ int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_
   a.accept_len = accept_len; a.accept_path = accept_path; a.recover_tok = recover_tok; a.last_node = last_node;
   a.exit_flag = exit_flag; a.new_ctx_len = new_ctx_len;
   return check_hip(launch_accept_exit(a, static_cast<hipStream_t>(stream)), "accept_exit");
+}
+
+int32_t specexit_tree_gather(int32_t dtype, int32_t B, int32_t W_prev, int32_t top_b, int32_t W_next, int32_t D,
+                             int32_t n_q, const int32_t* src_row, const int32_t* rank, const int32_t* node,
+                             const int32_t* cand_tok, const void* hidden_prev, int32_t* tok_next,
+                             void* hidden_next, int32_t* block_tok, uint32_t flags, void* stream) {
+  (void)flags;
+  if (!dtype_ok(dtype)) return fail(SPECEXIT_EINVAL, "tree_gather: unknown dtype %d", dtype);
+  if (B < 1 || W_prev < 1 || W_next < 1 || B > 65535 || W_next > SPECEXIT_MAX_NQ || W_prev > SPECEXIT_MAX_NQ)
+    return fail(SPECEXIT_EINVAL, "tree_gather: B, W_prev or W_next out of range");
+  if (top_b < 1 || top_b > SPECEXIT_MAX_TOP_B) return fail(SPECEXIT_EINVAL, "tree_gather: top_b %d outside 1..%d", top_b, SPECEXIT_MAX_TOP_B);
+  if (n_q < 1 || n_q > SPECEXIT_MAX_NQ) return fail(SPECEXIT_EINVAL, "tree_gather: n_q %d outside 1..64", n_q);
+  if (!src_row || !rank || !node || !cand_tok || !tok_next) return fail(SPECEXIT_EINVAL, "tree_gather: a required pointer is null");
+  TreeGatherArgs a;
+  memset(&a, 0, sizeof(a));
+  a.B = B; a.W_prev = W_prev; a.top_b = top_b; a.W_next = W_next; a.n_q = n_q;
+  a.src_row = src_row; a.rank = rank; a.node = node; a.cand_tok = cand_tok; a.tok_next = tok_next;
+  a.block_tok = block_tok;
+  if (hidden_next) {
+    if (!hidden_prev || hidden_prev == hidden_next) return fail(SPECEXIT_EINVAL, "tree_gather: hidden_prev missing or aliasing hidden_next");
+    if (D < 1 || (D * esize(dtype)) % 16) return fail(SPECEXIT_EINVAL, "tree_gather: D * element size must be a multiple of 16");
+    a.hidden_prev = hidden_prev; a.hidden_next = hidden_next;
+    a.row_bytes = static_cast<int>(D * esize(dtype));
+  }
+  return check_hip(launch_tree_gather(a, static_cast<hipStream_t>(stream)), "tree_gather");
 }
 
 int32_t specexit_kv_compact(const specexit_kv_view* kv, int32_t n_layers, int64_t layer_stride_bytes, int32_t B,

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
   const int G = a.Hq / a.Hkv;
   const int R = G * a.n_q;
   const int L = a.ctx_len[b];
-  const int total = L + a.n_q;
+  const int total = L + a.n_blk;
   const int s0 = split * a.chunk;
   if (s0 >= total) return;
   const int s1 = min(total, s0 + a.chunk);
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
       bool vis = p < s1;
       if (vis && p >= L) {
         const int i = r / G;
-        const uint64_t row = a.mask ? a.mask[static_cast<size_t>(b) * a.n_q + i] : ((2ull << i) - 1ull);
+        const uint64_t row = a.mask ? a.mask[static_cast<size_t>(b) * a.mask_stride + i] : ((2ull << i) - 1ull);
         vis = (row >> (p - L)) & 1ull;
       }
       float acc = 0.f;
@@ -178,7 +178,7 @@ __global__ __launch_bounds__(64) void k_attn_combine(const AttnArgs a) {
   const int G = a.Hq / a.Hkv;
   const int R = G * a.n_q;
   const int g = h / G, r = i * G + h % G;
-  const int total = a.ctx_len[b] + a.n_q;
+  const int total = a.ctx_len[b] + a.n_blk;
   const int nact = (total + a.chunk - 1) / a.chunk;
   const size_t unit0 = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit;
   const float* ml = a.part_ml + (unit0 * R + r) * 2;          // chunk s at ml[s * R * 2]

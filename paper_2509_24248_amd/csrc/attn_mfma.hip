@@ -89,7 +89,7 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   const int G = a.Hq / a.Hkv;
   const int R = G * a.n_q;
   const int L = a.ctx_len[b];
-  const int total = L + a.n_q;
+  const int total = L + a.n_blk;
   const int s0 = split * a.chunk;
   if (s0 >= total) return;  // the whole workgroup leaves together
   const int s1 = min(total, s0 + a.chunk);
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks)
       qf[ks][t] = valid ? *reinterpret_cast<const uint4*>(qp + ks * 32) : make_uint4(0, 0, 0, 0);
-    rowmask[t] = !valid ? 0ull : (a.mask ? a.mask[static_cast<size_t>(b) * a.n_q + i] : ((2ull << i) - 1ull));
+    rowmask[t] = !valid ? 0ull : (a.mask ? a.mask[static_cast<size_t>(b) * a.mask_stride + i] : ((2ull << i) - 1ull));
   }
 
   // ---- page ids of the chunk, copied to LDS once: loads from there do not count against

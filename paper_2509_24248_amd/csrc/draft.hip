@@ -125,24 +125,30 @@ __global__ __launch_bounds__(kNormThreads) void k_reduce_norm(int B, int N, cons
   }
 }
 
+// Row r of the step belongs to sequence r / W.  Its rotary position is pos[r / W] + level and
+// its K/V go to cache entry pos[r / W] + node[r % W] (chain step: W = 1, level 0, node null
+// = entry pos itself; tree level: position = context + depth, entry = context + node id).
 template <typename T>
-__global__ void k_rope_kvwrite(int B, int Hq, int Hkv, int d, const float* __restrict__ partial,
-                               int nslices, int planes, const int32_t* __restrict__ pos, float theta,
+__global__ void k_rope_kvwrite(int M, int W, int Hq, int Hkv, int d, const float* __restrict__ partial,
+                               int nslices, int planes, const int32_t* __restrict__ pos, int level,
+                               const int32_t* __restrict__ node, float theta,
                                T* __restrict__ q_out, int paged, T* __restrict__ kc, T* __restrict__ vc,
                                const int32_t* __restrict__ page_table, int page_size, int max_pages,
                                int64_t l_max) {
-  const int b = blockIdx.x, hh = blockIdx.y, c = threadIdx.x;  // c in [0, d/2)
+  const int r = blockIdx.x, hh = blockIdx.y, c = threadIdx.x;  // c in [0, d/2)
+  const int b = r / W;
   const int N = (Hq + 2 * Hkv) * d;
-  const int Mv = B * planes;
+  const int Mv = M * planes;
   const int half = d >> 1;
   float x1 = 0.f, x2 = 0.f;
   for (int ks = 0; ks < nslices; ++ks)
     for (int p = 0; p < planes; ++p) {
-      const float* src = partial + (static_cast<size_t>(ks) * Mv + b * planes + p) * N + hh * d;
+      const float* src = partial + (static_cast<size_t>(ks) * Mv + r * planes + p) * N + hh * d;
       x1 += src[c];
       x2 += src[c + half];
     }
-  const int ps = pos[b];
+  const int ps = pos[b] + level;
+  const int slot = pos[b] + (node ? node[r % W] : 0);
   if (hh < Hq + Hkv) {
     // rotary embedding, pairing (c, c + d/2); the angle is formed in double so that long
     // positions keep their phase
@@ -155,19 +161,20 @@ __global__ void k_rope_kvwrite(int B, int Hq, int Hkv, int d, const float* __res
     x2 = r2;
   }
   if (hh < Hq) {
-    T* dst = q_out + (static_cast<size_t>(b) * Hq + hh) * d;
+    T* dst = q_out + (static_cast<size_t>(r) * Hq + hh) * d;
     Elem<T>::store(dst + c, x1);
     Elem<T>::store(dst + c + half, x2);
     return;
   }
+  if (slot < 0 || slot >= l_max) return;       // an entry outside the cache is not written
   const bool is_k = hh < Hq + Hkv;
   const int h = is_k ? hh - Hq : hh - Hq - Hkv;
   size_t off;
   if (paged) {
-    const int page = page_table[static_cast<size_t>(b) * max_pages + ps / page_size];
-    off = ((static_cast<size_t>(page) * Hkv + h) * page_size + ps % page_size) * d;
+    const int page = page_table[static_cast<size_t>(b) * max_pages + slot / page_size];
+    off = ((static_cast<size_t>(page) * Hkv + h) * page_size + slot % page_size) * d;
   } else {
-    off = ((static_cast<size_t>(b) * Hkv + h) * l_max + ps) * d;
+    off = ((static_cast<size_t>(b) * Hkv + h) * l_max + slot) * d;
   }
   T* dst = (is_k ? kc : vc) + off;
   Elem<T>::store(dst + c, x1);
@@ -237,19 +244,19 @@ hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* pa
   return hipGetLastError();
 }
 
-hipError_t launch_rope_kvwrite(const DraftDims& dm, int B, const float* partial, int nslices,
-                               int planes, const int32_t* pos, void* q_out, int kv_paged, void* kc,
-                               void* vc, const int32_t* page_table, int page_size, int max_pages,
-                               int64_t l_max, hipStream_t s) {
-  const dim3 grid(B, dm.Hq + 2 * dm.Hkv), block(dm.d / 2);
+hipError_t launch_rope_kvwrite(const DraftDims& dm, int M, int W, const float* partial, int nslices,
+                               int planes, const int32_t* pos, int level, const int32_t* node, void* q_out,
+                               int kv_paged, void* kc, void* vc, const int32_t* page_table, int page_size,
+                               int max_pages, int64_t l_max, hipStream_t s) {
+  const dim3 grid(M, dm.Hq + 2 * dm.Hkv), block(dm.d / 2);
   if (dm.dtype == 1)
-    hipLaunchKernelGGL(k_rope_kvwrite<bf16_t>, grid, block, 0, s, B, dm.Hq, dm.Hkv, dm.d, partial, nslices, planes,
-                       pos, dm.rope_theta, static_cast<bf16_t*>(q_out), kv_paged, static_cast<bf16_t*>(kc),
-                       static_cast<bf16_t*>(vc), page_table, page_size, max_pages, l_max);
+    hipLaunchKernelGGL(k_rope_kvwrite<bf16_t>, grid, block, 0, s, M, W, dm.Hq, dm.Hkv, dm.d, partial, nslices, planes,
+                       pos, level, node, dm.rope_theta, static_cast<bf16_t*>(q_out), kv_paged,
+                       static_cast<bf16_t*>(kc), static_cast<bf16_t*>(vc), page_table, page_size, max_pages, l_max);
   else
-    hipLaunchKernelGGL(k_rope_kvwrite<float>, grid, block, 0, s, B, dm.Hq, dm.Hkv, dm.d, partial, nslices, planes,
-                       pos, dm.rope_theta, static_cast<float*>(q_out), kv_paged, static_cast<float*>(kc),
-                       static_cast<float*>(vc), page_table, page_size, max_pages, l_max);
+    hipLaunchKernelGGL(k_rope_kvwrite<float>, grid, block, 0, s, M, W, dm.Hq, dm.Hkv, dm.d, partial, nslices, planes,
+                       pos, level, node, dm.rope_theta, static_cast<float*>(q_out), kv_paged,
+                       static_cast<float*>(kc), static_cast<float*>(vc), page_table, page_size, max_pages, l_max);
   return hipGetLastError();
 }
 

@@ -231,7 +231,9 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
     }
     return;
   }
-  // head mode: fused argmax over rows < V, signal rows routed to extra_out
+  // head mode: fused argmax (or the top_b best, best first) over rows < V of this tile,
+  // signal rows routed to extra_out
+  const int TB = g.top_b > 1 ? g.top_b : 1;
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
     const int v = 16 * t + fr;
@@ -243,29 +245,41 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
     }
     const bool owner = (v < Mv) && (PLANES == 1 || (fr & 1) == 0);
     const int m = v / PLANES;
-    float bv = -INFINITY;
-    int bi = INT_MAX;
+    float cur[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int n = n0 + 4 * fq + i;
+      cur[i] = -INFINITY;
       if (owner && n < g.N) {
         if (n < g.V) {
           if (g.logits_dbg) g.logits_dbg[static_cast<size_t>(m) * g.V + n] = val[i];
-          if (val[i] > bv) { bv = val[i]; bi = n; }
+          cur[i] = val[i];
         } else if (g.extra_out) {
           g.extra_out[m * g.n_extra + (n - g.V)] = val[i];
         }
       }
     }
+    for (int r = 0; r < TB; ++r) {
+      float bv = -INFINITY;
+      int bi = INT_MAX;
 #pragma unroll
-    for (int o = 16; o < 64; o <<= 1) {
-      const float ov = __shfl_xor(bv, o, 64);
-      const int oi = __shfl_xor(bi, o, 64);
-      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-    }
-    if (owner && fq == 0) {
-      g.part_val[static_cast<size_t>(m) * ntiles + tile] = bv;
-      g.part_idx[static_cast<size_t>(m) * ntiles + tile] = bi;
+      for (int i = 0; i < 4; ++i)
+        if (cur[i] > bv) { bv = cur[i]; bi = n0 + 4 * fq + i; }
+#pragma unroll
+      for (int o = 16; o < 64; o <<= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+      }
+      if (owner && fq == 0) {
+        g.part_val[(static_cast<size_t>(m) * ntiles + tile) * TB + r] = bv;
+        g.part_idx[(static_cast<size_t>(m) * ntiles + tile) * TB + r] = bi;
+      }
+      if (r + 1 < TB) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (n0 + 4 * fq + i == bi) cur[i] = -INFINITY;   // taken: out of the next pass
+      }
     }
   }
 }
@@ -304,6 +318,63 @@ __global__ __launch_bounds__(kFinalThreads) void k_argmax_finalize(const float* 
       if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
     argmax[m] = bi;
     if (max_logit) max_logit[m] = bv;
+  }
+  if (sig && threadIdx.x == 64) {
+    const float zc = extra[m * 3 + 0], zp = extra[m * 3 + 1], zr = extra[m * 3 + 2];
+    sig_raw[m * 3 + 0] = zc; sig_raw[m * 3 + 1] = zp; sig_raw[m * 3 + 2] = zr;
+    sig[m * 3 + 0] = sigmoidf_(zc);
+    sig[m * 3 + 1] = sigmoidf_(zp);
+    sig[m * 3 + 2] = rem_activation == 0 ? fmaxf(0.f, expm1f(zr)) : (rem_activation == 1 ? sigmoidf_(zr) : zr);
+  }
+}
+
+// The top_b best of each row, best first (value descending, lower index first among equals),
+// from per-tile candidates (part_idx != nullptr: C = ntiles * top_b pairs, INT_MAX marks an
+// empty slot) or from a full logits row (part_idx == nullptr: candidate c is (row[c], c)).
+// Pass r takes the best candidate that comes after pass r-1's pick in that order.
+__global__ __launch_bounds__(kFinalThreads) void k_topb_finalize(const float* __restrict__ vals,
+                                                                 const int* __restrict__ idxs, int C, int stride,
+                                                                 int top_b, int32_t* __restrict__ cand_tok,
+                                                                 float* __restrict__ cand_logit,
+                                                                 const float* __restrict__ extra, int rem_activation,
+                                                                 float* __restrict__ sig_raw, float* __restrict__ sig) {
+  __shared__ float sv[kFinalThreads / 64];
+  __shared__ int si[kFinalThreads / 64];
+  __shared__ float pick_v;
+  __shared__ int pick_i;
+  const int m = blockIdx.x;
+  const float* rv = vals + static_cast<size_t>(m) * stride;
+  const int* ri = idxs ? idxs + static_cast<size_t>(m) * stride : nullptr;
+  float prev_v = INFINITY;
+  int prev_i = -1;
+  for (int r = 0; r < top_b; ++r) {
+    float bv = -INFINITY;
+    int bi = INT_MAX;
+    for (int c = threadIdx.x; c < C; c += kFinalThreads) {
+      const float v = rv[c];
+      const int i = ri ? ri[c] : c;
+      const bool after = v < prev_v || (v == prev_v && i > prev_i);
+      if (i != INT_MAX && after && better(v, i, bv, bi)) { bv = v; bi = i; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(bv, o, 64);
+      const int oi = __shfl_xor(bi, o, 64);
+      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int w = 1; w < kFinalThreads / 64; ++w)
+        if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
+      cand_tok[m * top_b + r] = bi == INT_MAX ? -1 : bi;
+      if (cand_logit) cand_logit[m * top_b + r] = bv;
+      pick_v = bv;
+      pick_i = bi;
+    }
+    __syncthreads();
+    prev_v = pick_v;
+    prev_i = pick_i;
   }
   if (sig && threadIdx.x == 64) {
     const float zc = extra[m * 3 + 0], zp = extra[m * 3 + 1], zr = extra[m * 3 + 2];
@@ -443,6 +514,14 @@ hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, in
                                   int rem_activation, float* sig_raw, float* sig) {
   hipLaunchKernelGGL(k_argmax_finalize, dim3(M), dim3(kFinalThreads), 0, s, part_val, part_idx, ntiles, argmax,
                      max_logit, extra, rem_activation, sig_raw, sig);
+  return hipGetLastError();
+}
+
+hipError_t launch_topb_finalize(const float* vals, const int* idxs, int C, int stride, int top_b, int M,
+                                int32_t* cand_tok, float* cand_logit, hipStream_t s, const float* extra,
+                                int rem_activation, float* sig_raw, float* sig) {
+  hipLaunchKernelGGL(k_topb_finalize, dim3(M), dim3(kFinalThreads), 0, s, vals, idxs, C, stride, top_b, cand_tok,
+                     cand_logit, extra, rem_activation, sig_raw, sig);
   return hipGetLastError();
 }
 

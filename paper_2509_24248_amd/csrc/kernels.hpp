@@ -30,8 +30,9 @@ struct GemmArgs {
   float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
   int V;               // head mode when >= 0
   int n_extra;
-  float* part_val;     // head mode: [M][ntiles] best value per 16-row tile
-  int* part_idx;       //            [M][ntiles] its row index
+  int top_b;           // head mode: candidates kept per tile (0 or 1 = the argmax only)
+  float* part_val;     // head mode: [M][ntiles][top_b] best values per 16-row tile, best first
+  int* part_idx;       //            [M][ntiles][top_b] their row indices (INT_MAX = none)
   float* extra_out;    // [M][n_extra] or nullptr
   float* logits_dbg;   // [M][V] or nullptr
 };
@@ -49,6 +50,12 @@ hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, in
                                   int32_t* argmax, float* max_logit, hipStream_t s,
                                   const float* extra = nullptr, int rem_activation = 0,
                                   float* sig_raw = nullptr, float* sig = nullptr);
+// the top_b best per row, best first, from per-tile candidates (idxs given; C pairs per row)
+// or from full rows of logits (idxs null; C = V values per row); rows lie `stride` apart
+hipError_t launch_topb_finalize(const float* vals, const int* idxs, int C, int stride, int top_b, int M,
+                                int32_t* cand_tok, float* cand_logit, hipStream_t s,
+                                const float* extra = nullptr, int rem_activation = 0,
+                                float* sig_raw = nullptr, float* sig = nullptr);
 // VALU head path: logits [M][N] -> argmax over n < V, copy of signal rows and of logits
 hipError_t launch_argmax_rows(const float* logits, int M, int N, int V, int n_extra,
                               int32_t* argmax, float* max_logit, float* extra_out,
@@ -68,6 +75,9 @@ struct AttnArgs {
   const void* q;             // [B, n_q, Hq, d]
   const int32_t* ctx_len;    // [B] number of context entries before the block
   const uint64_t* mask;      // [B, n_q] or nullptr = chain
+  int n_blk;                 // block entries stored after the context (normally n_q; tree drafting:
+                             // every node written so far, of which n_q are this call's queries)
+  int mask_stride;           // mask words between two sequences' rows (n_q; 0 = all sequences share)
   float scale;
   void* out;                 // [B, n_q, Hq, d] in dtype
   int chunk;                 // keys per split
@@ -98,10 +108,11 @@ hipError_t launch_embed_concat(const DraftDims& dm, int B, const void* embed, co
 hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* partial, int nslices,
                               int planes, const float* residual, const void* gain, float* sum_out,
                               void* hidden_out, float* act, hipStream_t s);
-hipError_t launch_rope_kvwrite(const DraftDims& dm, int B, const float* partial, int nslices,
-                               int planes, const int32_t* pos, void* q_out, int kv_paged, void* kc,
-                               void* vc, const int32_t* page_table, int page_size, int max_pages,
-                               int64_t l_max, hipStream_t s);
+// rows r = b * W + w: rotary position pos[b] + level, cache entry pos[b] + node[w] (node null: pos[b])
+hipError_t launch_rope_kvwrite(const DraftDims& dm, int M, int W, const float* partial, int nslices,
+                               int planes, const int32_t* pos, int level, const int32_t* node, void* q_out,
+                               int kv_paged, void* kc, void* vc, const int32_t* page_table, int page_size,
+                               int max_pages, int64_t l_max, hipStream_t s);
 hipError_t launch_silu_mul(const DraftDims& dm, int B, const float* partial, int nslices, int planes,
                            float* act, hipStream_t s);
 hipError_t launch_head_finalize(const DraftDims& dm, int B, const int32_t* argmax_in,
@@ -128,6 +139,19 @@ struct CompactArgs {
 };
 bool kv_compact_supported(const CompactArgs& a);
 hipError_t launch_kv_compact(const CompactArgs& a, hipStream_t s);
+
+// ---- tree drafting: hand tokens and hidden states from one level to the next ----------------
+struct TreeGatherArgs {
+  int B, W_prev, top_b, W_next, n_q;
+  int row_bytes;               // D * element size
+  const int32_t *src_row, *rank, *node;   // [W_next]
+  const int32_t* cand_tok;     // [B][W_prev][top_b]
+  const void* hidden_prev;     // [B][W_prev][row_bytes]
+  int32_t* tok_next;           // [B][W_next]
+  void* hidden_next;           // [B][W_next][row_bytes] or nullptr
+  int32_t* block_tok;          // [B][n_q] or nullptr
+};
+hipError_t launch_tree_gather(const TreeGatherArgs& a, hipStream_t s);
 
 // ---- controller ------------------------------------------------------------------------
 constexpr int kSmoothWords = 48;   // 3 signals x 16 words

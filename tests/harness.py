@@ -140,9 +140,102 @@ class GpuDraft:
     def cache(self):
         return host(self.keep[0]), host(self.keep[1])
 
+    def tree(self, tok0, g0, ctx_len, parent, rank, top_b):
+        """Draft a whole tree level by level through specexit_draft_tree_level / specexit_tree_gather.
+        Only index arrays are prepared here; every value comes out of the library."""
+        lib, shape, B = self.lib, self.shape, self.shape.B
+        n = len(parent)
+        depth = O.tree_depths(parent)
+        expanded = [any(int(parent[c]) == p for c in range(1, n)) for p in range(n)]
+        masks = gen.ancestor_masks(np.asarray(parent)[None, :])[0]
+        i32 = lambda a: dev(np.asarray(a, np.int32))
+        dt = lib.BF16 if shape.dtype == "bf16" else lib.F32
+        Wmax = max(sum(1 for c in range(n) if depth[c] == l and expanded[c]) for l in range(int(depth.max()) + 1))
+        ws = workspace(lib.specexit_draft_tree_level_workspace_bytes(self.desc, self.view, B, Wmax, top_b))
+        assert ws.numel() > 256, lib.last_error()
+        ctx = i32(ctx_len)
+        block_tok = torch.zeros((B, n), dtype=torch.int32, device="cuda")
+        block_tok[:, 0] = i32(tok0)
+        tok = i32(tok0).reshape(B, 1).contiguous()
+        hid = dev(g0, shape).reshape(B, 1, shape.D).contiguous()
+        rows = [0]
+        res = {"hidden_out": {}, "cand_tok": {}, "cand_logit": {}, "sig_raw": {}, "sig": {}}
+        for level in range(int(depth.max())):
+            W = len(rows)
+            hout = torch.empty((B, W, shape.D), dtype=tdtype(shape), device="cuda")
+            ct = torch.empty((B, W, top_b), dtype=torch.int32, device="cuda")
+            cl = torch.empty((B, W, top_b), dtype=torch.float32, device="cuda")
+            sr = torch.empty((B, W, 3), dtype=torch.float32, device="cuda")
+            sg = torch.empty((B, W, 3), dtype=torch.float32, device="cuda")
+            print(f"  tree level {level}: rows {rows}", flush=True)
+            lib.specexit_draft_tree_level(self.desc, self.w, self.view, B, W, tok, hid, ctx, level, i32(rows),
+                                          dev(masks[rows]), max(rows) + 1, top_b, hout, ct, cl, sr, sg, ws)
+            torch.cuda.synchronize()
+            for j, c in enumerate(rows):
+                res["hidden_out"][c], res["cand_tok"][c], res["cand_logit"][c] = host(hout[:, j]), host(ct[:, j]), host(cl[:, j])
+                res["sig_raw"][c], res["sig"][c] = host(sr[:, j]), host(sg[:, j])
+            kids = [c for c in range(n) if depth[c] == level + 1]
+            src = [rows.index(int(parent[c])) for c in kids]
+            all_tok = torch.empty((B, len(kids)), dtype=torch.int32, device="cuda")
+            lib.specexit_tree_gather(dt, B, W, top_b, len(kids), shape.D, n, i32(src), i32([rank[c] for c in kids]),
+                                     i32(kids), ct, hout, all_tok, None, block_tok)
+            nxt = [c for c in kids if expanded[c]]
+            if not nxt:
+                break
+            src = [rows.index(int(parent[c])) for c in nxt]
+            tok = torch.empty((B, len(nxt)), dtype=torch.int32, device="cuda")
+            hid = torch.empty((B, len(nxt), shape.D), dtype=tdtype(shape), device="cuda")
+            lib.specexit_tree_gather(dt, B, W, top_b, len(nxt), shape.D, n, i32(src), i32([rank[c] for c in nxt]),
+                                     i32(nxt), ct, hout, tok, hid, None)
+            rows = nxt
+        torch.cuda.synchronize()
+        res["block_tok"] = host(block_tok)
+        return res
+
 
 def oracle_dims(shape):
     return O.DraftDims(shape.D, shape.Hq, shape.Hkv, shape.d, shape.V, shape.rms_eps, shape.rope_theta)
+
+
+def oracle_tree(shape, w, kv, tok0, g0, L, parent, rank):
+    kc, vc = kv.k.astype(np.float64), kv.v.astype(np.float64)
+    out = O.draft_tree(oracle_dims(shape), w, kc, vc, tok0, g0, L, parent, rank, kv.page_table if kv.paged else None,
+                       kv.page_size, store=lambda a: gen.store(shape, np.asarray(a, np.float32)))
+    return out, kc, vc
+
+
+def force_tree_gap(shape, w, kv, tok0, g0, L, parent, rank, top_b, gap=0.05, max_iter=12):
+    """Bump w_head until, at every expanded node, the top_b + 1 best logits lie more than `gap`
+    apart (with the oracle's logits), so that float32 / bf16 arithmetic cannot reorder them."""
+    w = dict(w)
+    V = shape.V
+    for _ in range(max_iter):
+        out, kc, vc = oracle_tree(shape, w, kv, tok0, g0, L, parent, rank)
+        head = w["w_head"].copy()
+        bad = 0
+        for b in range(shape.B):
+            for c in np.flatnonzero(out["expanded"]):
+                z = out["logits"][b, c]
+                order = O.top_b_lowest(z, top_b + 1)
+                gaps = z[order[:-1]] - z[order[1:]]
+                if gaps.min() >= gap * 1.2:
+                    continue
+                bad += 1
+                h = out["h_final"][b, c]
+                inc = 0.0                                # raise only what is missing, from the bottom up
+                for r in range(top_b - 1, -1, -1):
+                    inc += max(0.0, 1.6 * gap - (z[order[r]] - z[order[r + 1]]))
+                    if inc > 0.0:
+                        # spend the bump on the 64 largest components of h: spread over all of
+                        # them it would be below the storage type's rounding step
+                        big = np.argsort(-np.abs(h))[:64]
+                        row = head[order[r]].astype(np.float64)
+                        row[big] += inc * h[big] / (h[big] @ h[big])
+                        head[order[r]] = gen.store(shape, row.astype(np.float32))
+        if bad == 0:
+            return w, out, kc, vc
+        w["w_head"] = head
+    raise AssertionError("could not force the logit gaps of the tree")
 
 
 def force_draft_gap(shape, w, kv, tok, g, pos, gap=0.05):

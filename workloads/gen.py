@@ -301,6 +301,29 @@ def random_tree_parents(shape: Shape, seed: int = 0, max_children: int = 3) -> n
     return out
 
 
+def level_ordered_tree(shape: Shape, seed: int = 0, max_children: int = 3):
+    """One draft-tree topology for tree drafting, shared by the sequences: a random tree as
+    above, renumbered level by level (parents keep their relative order), with rank[c] = the
+    position of c among its siblings.  Returns (parent [n], rank [n])."""
+    one = replace(shape, B=1)
+    old = random_tree_parents(one, seed, max_children)[0]
+    n = len(old)
+    depth = np.zeros(n, np.int64)
+    for c in range(1, n):
+        depth[c] = depth[old[c]] + 1
+    order = sorted(range(n), key=lambda c: (depth[c], c))
+    new_id = {c: i for i, c in enumerate(order)}
+    parent = np.full(n, -1, np.int32)
+    for c in range(1, n):
+        parent[new_id[c]] = new_id[int(old[c])]
+    rank = np.zeros(n, np.int32)
+    seen = {}
+    for c in range(1, n):
+        rank[c] = seen.get(int(parent[c]), 0)
+        seen[int(parent[c])] = rank[c] + 1
+    return parent, rank
+
+
 def ancestor_masks(parent: np.ndarray) -> np.ndarray:
     """mask[b, i] bit j set iff node j is node i or one of its ancestors."""
     B, n = parent.shape
