@@ -223,6 +223,7 @@ int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specex
 struct DraftBufs {
   float* act;
   float* partial;
+  float* partial2;   // the down projection's partial sums (its input lives in `partial`)
   float *x_buf, *a_buf;
   void *q_buf, *attn_out;
   void* attn_ws;
@@ -230,6 +231,9 @@ struct DraftBufs {
   int* part_idx;
   int32_t* head_am;
   float* extra;
+  float* ssq;        // [3][rows][groups of D]: pieces of the sums of squares behind the three norms
+  int* counters;     // arrival counters of the reducing GEMM epilogues
+  int n_counters;
   size_t total;
 };
 
@@ -239,6 +243,7 @@ DraftBufs carve_draft(const DraftPlan& p, void* ws) {
   const size_t es = esize(p.dm.dtype);
   b.act = c.take<float>(sizeof(float) * p.B * p.Kmax);
   b.partial = c.take<float>(p.partial_bytes);
+  b.partial2 = c.take<float>(p.mfma ? partial_bytes_of(p.down, true) : 0);
   b.x_buf = c.take<float>(sizeof(float) * p.B * p.dm.D);
   b.a_buf = c.take<float>(sizeof(float) * p.B * p.dm.D);
   b.q_buf = c.take<char>(es * p.B * p.dm.Hq * p.dm.d);
@@ -248,6 +253,10 @@ DraftBufs carve_draft(const DraftPlan& p, void* ws) {
   b.part_idx = c.take<int>(sizeof(int) * p.B * p.ntiles_head * p.top_b);
   b.head_am = c.take<int32_t>(sizeof(int32_t) * p.B);
   b.extra = c.take<float>(sizeof(float) * p.B * 3);
+  const int gd = gemm_groups(p.dm.D);
+  b.ssq = c.take<float>(sizeof(float) * 3 * p.B * gd);
+  b.n_counters = 3 * gd;
+  b.counters = c.take<int>(sizeof(int) * b.n_counters);
   b.total = c.off;
   return b;
 }
@@ -297,20 +306,46 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
   const bool bf16 = dm.dtype == SPECEXIT_BF16;
   const bool mf = p.mfma;
 
-  // x = W_fc [embed[tok] ; hidden_in]
+  const int gd = gemm_groups(dm.D);
   if (mf) {
+    // Fused form: each projection back into the hidden size finishes its own split-K sums
+    // (+ residual) in the workgroup that arrives last, leaving the rows and the pieces of
+    // their sums of squares; the next GEMM applies the RMSNorm while it stages its activations,
+    // and the down projection applies the SiLU gate the same way.
+    if ((rc = check_hip(launch_zero_i32(b.counters, b.n_counters, s), "zero counters"))) return rc;
+    auto reducing = [&](GemmArgs& g, int which, const float* residual, float* out_x, void* out_store) {
+      g.epi = 1;
+      g.counters = b.counters + which * gd;
+      g.residual = residual;
+      g.out_x = out_x;
+      g.out_store = out_store;
+      g.out_ssq = b.ssq + static_cast<size_t>(which) * B * gd;
+    };
+    auto normed = [&](GemmArgs& g, int which, const float* x, const void* gain) {
+      g.a_mode = 3;
+      g.a_src = x;
+      g.a_ssq = b.ssq + static_cast<size_t>(which) * B * gd;
+      g.a_nssq = gd;
+      g.a_gain = gain;
+      g.a_eps = dm.rms_eps;
+    };
+    // x = W_fc [embed[tok] ; hidden_in]
     p.fc.a_mode = 2;   // the GEMM gathers [embed[tok] ; hidden_in] itself
     p.fc.a_src = io.hidden_in;
     p.fc.a_embed = w->embed;
     p.fc.a_tok = io.tok;
+    reducing(p.fc, 0, nullptr, b.x_buf, nullptr);
+    if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
+    // q, k, v; rotary; cache write; attention over the draft's own cache
+    normed(p.qkv, 0, b.x_buf, w->ln_attn);
+    if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
   } else {
     if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, io.tok, io.hidden_in, b.act, s), "embed_concat"))) return rc;
+    if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
+    if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.fc.ksplit, p.fc.planes, nullptr, w->ln_attn,
+                                           b.x_buf, nullptr, b.act, s), "norm attn"))) return rc;
+    if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
   }
-  if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
-  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.fc.ksplit, p.fc.planes, nullptr, w->ln_attn,
-                                         b.x_buf, nullptr, b.act, s), "norm attn"))) return rc;
-  // q, k, v; rotary; cache write; attention over the draft's own cache
-  if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
   if ((rc = check_hip(launch_rope_kvwrite(dm, B, p.W, b.partial, p.qkv.ksplit, p.qkv.planes, io.pos, io.level, io.node,
                                           b.q_buf, p.attn.paged, draft_kv->k, draft_kv->v, draft_kv->page_table,
                                           p.attn.page_size, p.attn.max_pages, p.attn.l_max, s), "rope"))) return rc;
@@ -330,22 +365,58 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     at.part_ml = c.take<float>(units * R * 2 * sizeof(float));
   }
   if ((rc = check_hip(launch_attn(at, s, &g_prof_hook, SPECEXIT_PROF_DRAFT_ATTN), "draft attention"))) return rc;
-  // a = x + W_o attn
   if (mf) {
+    // a = x + W_o attn
     p.o.a_mode = 1;    // attention output is read in its storage type
     p.o.a_src = b.attn_out;
+    p.o.epi = 1;
+    p.o.counters = b.counters + gd;
+    p.o.residual = b.x_buf;
+    p.o.out_x = b.a_buf;
+    p.o.out_ssq = b.ssq + static_cast<size_t>(1) * B * gd;
+    if ((rc = run_gemm(p.o, mf, bf16, w->w_o, nullptr, nullptr, b, s, "gemm o"))) return rc;
+    // y = a + W_down (silu(W_gate m) * W_up m), m = RMSNorm(a)
+    p.gu.a_mode = 3;
+    p.gu.a_src = b.a_buf;
+    p.gu.a_ssq = p.o.out_ssq;
+    p.gu.a_nssq = gd;
+    p.gu.a_gain = w->ln_mlp;
+    p.gu.a_eps = dm.rms_eps;
+    if ((rc = run_gemm(p.gu, mf, bf16, w->w_gate, w->w_up, nullptr, b, s, "gemm gate/up"))) return rc;
+    // the down projection needs its own partial buffer: its input is the gate/up partial sums
+    p.down.a_mode = 4;
+    p.down.a_src = b.partial;
+    p.down.a_nslices = p.gu.ksplit * p.gu.planes;
+    p.down.a_src_planes = p.gu.planes;
+    p.down.epi = 1;
+    p.down.counters = b.counters + 2 * gd;
+    p.down.residual = b.a_buf;
+    p.down.out_x = b.x_buf;            // y (x is no longer needed)
+    p.down.out_store = io.hidden_out;
+    p.down.out_ssq = b.ssq + static_cast<size_t>(2) * B * gd;
+    {
+      GemmArgs g = p.down;
+      g.w[0] = w->w_down;
+      g.partial = b.partial2;
+      if ((rc = check_hip(launch_gemm_mfma(g, s), "gemm down"))) return rc;
+    }
+    p.head.a_mode = 3;
+    p.head.a_src = b.x_buf;
+    p.head.a_ssq = p.down.out_ssq;
+    p.head.a_nssq = gd;
+    p.head.a_gain = w->ln_final;
+    p.head.a_eps = dm.rms_eps;
   } else {
     if ((rc = check_hip(launch_unpack_rows(b.attn_out, bf16, B, dm.Hq * dm.d, b.act, s), "unpack attn"))) return rc;
+    if ((rc = run_gemm(p.o, mf, bf16, w->w_o, nullptr, nullptr, b, s, "gemm o"))) return rc;
+    if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.o.ksplit, p.o.planes, b.x_buf, w->ln_mlp,
+                                           b.a_buf, nullptr, b.act, s), "norm mlp"))) return rc;
+    if ((rc = run_gemm(p.gu, mf, bf16, w->w_gate, w->w_up, nullptr, b, s, "gemm gate/up"))) return rc;
+    if ((rc = check_hip(launch_silu_mul(dm, B, b.partial, p.gu.ksplit, p.gu.planes, b.act, s), "silu"))) return rc;
+    if ((rc = run_gemm(p.down, mf, bf16, w->w_down, nullptr, nullptr, b, s, "gemm down"))) return rc;
+    if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.down.ksplit, p.down.planes, b.a_buf, w->ln_final,
+                                           nullptr, io.hidden_out, b.act, s), "norm final"))) return rc;
   }
-  if ((rc = run_gemm(p.o, mf, bf16, w->w_o, nullptr, nullptr, b, s, "gemm o"))) return rc;
-  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.o.ksplit, p.o.planes, b.x_buf, w->ln_mlp,
-                                         b.a_buf, nullptr, b.act, s), "norm mlp"))) return rc;
-  // y = a + W_down (silu(W_gate m) * W_up m)
-  if ((rc = run_gemm(p.gu, mf, bf16, w->w_gate, w->w_up, nullptr, b, s, "gemm gate/up"))) return rc;
-  if ((rc = check_hip(launch_silu_mul(dm, B, b.partial, p.gu.ksplit, p.gu.planes, b.act, s), "silu"))) return rc;
-  if ((rc = run_gemm(p.down, mf, bf16, w->w_down, nullptr, nullptr, b, s, "gemm down"))) return rc;
-  if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.down.ksplit, p.down.planes, b.a_buf, w->ln_final,
-                                         nullptr, io.hidden_out, b.act, s), "norm final"))) return rc;
   // widened head (Eq. 1): argmax (or the top_b best) over the vocabulary rows, three signal rows on the side
   {
     ProfScope prof(SPECEXIT_PROF_DRAFT_HEAD_GEMM, s);

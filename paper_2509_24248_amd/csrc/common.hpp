@@ -67,6 +67,36 @@ __device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
   return v > bv || (v == bv && i < bi);
 }
 
+// Data handed from one workgroup to another inside a kernel (split-K partial sums that the
+// last workgroup to arrive adds up) is written and read at agent scope: the sc1 forms of the
+// store and load go through to the level all compute units of the device share, so no cache
+// has to be written back or invalidated as a whole (an agent-scope fence would do both).
+// The writer waits for its stores (s_waitcnt vmcnt(0)) before it signals through an atomic.
+typedef float f32x4v_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ void store_agent16(float* p, float a, float b, float c, float d) {
+  const f32x4v_t v = {a, b, c, d};
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void wait_stores() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// four independent 16-byte agent-scope loads, waited for together
+__device__ __forceinline__ void load_agent16x4(const float* p0, const float* p1, const float* p2, const float* p3,
+                                               float4 (&out)[4]) {
+  f32x4v_t a, b, c, d;
+  asm volatile(
+      "global_load_dwordx4 %0, %4, off sc1\n\t"
+      "global_load_dwordx4 %1, %5, off sc1\n\t"
+      "global_load_dwordx4 %2, %6, off sc1\n\t"
+      "global_load_dwordx4 %3, %7, off sc1\n\t"
+      "s_waitcnt vmcnt(0)"
+      : "=&v"(a), "=&v"(b), "=&v"(c), "=&v"(d)
+      : "v"(p0), "v"(p1), "v"(p2), "v"(p3)
+      : "memory");
+  out[0] = make_float4(a.x, a.y, a.z, a.w);
+  out[1] = make_float4(b.x, b.y, b.z, b.w);
+  out[2] = make_float4(c.x, c.y, c.z, c.w);
+  out[3] = make_float4(d.x, d.y, d.z, d.w);
+}
+
 __device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
 
 }  // namespace sx

@@ -106,17 +106,51 @@ __device__ __forceinline__ uint4 load_stream16(const char* p) {
 // entry ((s * 4 + q) * Mv + v) holds virtual row v's 8 values k0 + 32 s + 8 q .. + 7 as
 // bf16.  Virtual row v = m * PLANES + plane: plane 0 is the bf16 rounding of the value,
 // plane 1 the bf16 rounding of what that lost (fp32 activations keep ~16 mantissa bits).
+// rs_lds (mode 3): the rows' 1 / rms, computed once per workgroup.
 template <int PLANES>
-__device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_lds, int k0, int kc, int nthreads) {
+__device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_lds, const float* rs_lds, int k0, int kc,
+                                                  int nthreads) {
   const int Mv = g.M * PLANES;
   const int groups = kc >> 3;
   for (int idx = threadIdx.x; idx < g.M * groups; idx += nthreads) {
     const int m = idx / groups, g8 = idx - m * groups;
     const int k = k0 + g8 * 8;
     uint4 hi, lo = make_uint4(0, 0, 0, 0);
-    if (g.a_mode == 0) {
-      const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(g.a_src) + static_cast<size_t>(m) * g.K + k);
-      const float4 x = src[0], y = src[1];
+    if (g.a_mode == 0 || g.a_mode == 3 || g.a_mode == 4) {
+      float4 x, y;
+      if (g.a_mode == 4) {
+        // gate and up columns summed over the producer's slices, in slice order
+        float gt[8], up[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { gt[e] = 0.f; up[e] = 0.f; }
+        const int ld = 2 * g.K;
+        const float* base = static_cast<const float*>(g.a_src) + k;
+        const int splanes = g.a_src_planes;
+        for (int j = 0; j < g.a_nslices; ++j) {
+          const size_t row = static_cast<size_t>(j / splanes) * (g.M * splanes) + m * splanes + j % splanes;
+          const float4* pg = reinterpret_cast<const float4*>(base + row * ld);
+          const float4* pu = reinterpret_cast<const float4*>(base + row * ld + g.K);
+          const float4 a = pg[0], b = pg[1], c = pu[0], d = pu[1];
+          gt[0] += a.x; gt[1] += a.y; gt[2] += a.z; gt[3] += a.w; gt[4] += b.x; gt[5] += b.y; gt[6] += b.z; gt[7] += b.w;
+          up[0] += c.x; up[1] += c.y; up[2] += c.z; up[3] += c.w; up[4] += d.x; up[5] += d.y; up[6] += d.z; up[7] += d.w;
+        }
+        float f[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = gt[e] * sigmoidf_(gt[e]) * up[e];
+        x = make_float4(f[0], f[1], f[2], f[3]);
+        y = make_float4(f[4], f[5], f[6], f[7]);
+      } else {
+        const float4* src = reinterpret_cast<const float4*>(static_cast<const float*>(g.a_src) + static_cast<size_t>(m) * g.K + k);
+        x = src[0];
+        y = src[1];
+        if (g.a_mode == 3) {
+          float gn[8];
+          unpack16(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.a_gain) + k), gn);
+          const float rs = rs_lds[m];
+          x.x = x.x * rs * gn[0]; x.y = x.y * rs * gn[1]; x.z = x.z * rs * gn[2]; x.w = x.w * rs * gn[3];
+          y.x = y.x * rs * gn[4]; y.y = y.y * rs * gn[5]; y.z = y.z * rs * gn[6]; y.w = y.w * rs * gn[7];
+        }
+      }
       hi = make_uint4(pack_bf16x2(x.x, x.y), pack_bf16x2(x.z, x.w), pack_bf16x2(y.x, y.y), pack_bf16x2(y.z, y.w));
       if (PLANES == 2) {
         float f[8];
@@ -147,6 +181,15 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
   const int Mv = g.M * PLANES;
   uint4* a_lds = dyn_lds;
   uint4* w_lds = dyn_lds + (g.kc >> 3) * Mv;
+  float* rs_lds = reinterpret_cast<float*>(w_lds + kGemmWaves * 256);   // [M] 1 / rms of the rows (a_mode 3)
+  if (g.a_mode == 3) {
+    for (int m = threadIdx.x; m < g.M; m += 64 * kGemmWaves) {
+      float ssq = 0.f;
+      for (int j = 0; j < g.a_nssq; ++j) ssq += g.a_ssq[m * g.a_nssq + j];
+      rs_lds[m] = 1.0f / sqrtf(ssq / static_cast<float>(g.K) + g.a_eps);
+    }
+    __syncthreads();
+  }
   const int lane = threadIdx.x & 63;
   const int wv = threadIdx.x >> 6;
   const int ntiles = (g.N + 15) >> 4;
@@ -179,7 +222,7 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
   for (int c0 = kb0; c0 < kb1; c0 += kcb) {
     const int c1 = min(kb1, c0 + kcb);
     if (c0 != kb0) __syncthreads();    // everyone is done with the previous chunk
-    stage_activations<PLANES>(g, a_lds, c0 << 7, (c1 - c0) << 7, 64 * kGemmWaves);
+    stage_activations<PLANES>(g, a_lds, rs_lds, c0 << 7, (c1 - c0) << 7, 64 * kGemmWaves);
     __syncthreads();
     if (!active) continue;
     for (int kb = c0; kb < c1; ++kb) {
@@ -210,24 +253,106 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
       __builtin_amdgcn_wave_barrier();
     }
   }
-  if (!active) return;
+  if (!active && (HEAD || g.epi == 0)) return;
 
   // accumulator layout: lane (c = lane % 16, q = lane / 16) holds rows n0 + 4q + i of
   // activation column 16 t + c
   if (!HEAD) {
+    if (active) {
 #pragma unroll
-    for (int t = 0; t < MT; ++t) {
-      const int v = 16 * t + fr;
-      if (v < Mv) {
-        float* dst = g.partial + (static_cast<size_t>(ks) * Mv + v) * g.N + n0 + 4 * fq;
-        if (n0 + 4 * fq + 3 < g.N && (g.N & 3) == 0) {
-          *reinterpret_cast<float4*>(dst) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
-        } else {
+      for (int t = 0; t < MT; ++t) {
+        const int v = 16 * t + fr;
+        if (v < Mv) {
+          float* dst = g.partial + (static_cast<size_t>(ks) * Mv + v) * g.N + n0 + 4 * fq;
+          if (g.epi != 0) {
+            // read by another workgroup of this launch (N is a multiple of 4 here)
+            if (n0 + 4 * fq < g.N) store_agent16(dst, acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+          } else if (n0 + 4 * fq + 3 < g.N && (g.N & 3) == 0) {
+            *reinterpret_cast<float4*>(dst) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+          } else {
 #pragma unroll
-          for (int i = 0; i < 4; ++i)
-            if (n0 + 4 * fq + i < g.N) dst[i] = acc[t][i];
+            for (int i = 0; i < 4; ++i)
+              if (n0 + 4 * fq + i < g.N) dst[i] = acc[t][i];
+          }
         }
       }
+    }
+    if (g.epi == 0) return;
+    // ---- the workgroup that arrives last for this 128-row group reduces it.  The partial
+    // sums are written and read at agent scope; every wave waits for its stores, the
+    // workgroup meets, one thread takes a ticket, and the last workgroup reads all slices in a
+    // fixed order, so the sums do not depend on who is last.
+    __shared__ int s_last;
+    wait_stores();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int last = 1;
+      if (gridDim.y > 1) {
+        const int ticket = atomicAdd(&g.counters[blockIdx.x], 1);
+        last = ticket == static_cast<int>(gridDim.y) - 1;
+        if (last) g.counters[blockIdx.x] = 0;     // everyone has arrived: ready for the next launch
+      }
+      s_last = last;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    float4* red = reinterpret_cast<float4*>(dyn_lds);           // the tiles are done with: reuse their LDS
+    float* sq_lds = reinterpret_cast<float*>(red + 64 * kGemmWaves);
+    constexpr int NT = 64 * kGemmWaves;
+    const int items = g.M * 32;                                  // float4 outputs of the group
+    int lpi = 1;                                                 // threads sharing one output
+    while (lpi < 16 && items * lpi * 2 <= NT) lpi <<= 1;
+    const int nsl = static_cast<int>(gridDim.y) * PLANES;
+    const int n0g = blockIdx.x * (16 * kGemmWaves);
+    for (int base = 0; base < items; base += NT / lpi) {
+      const int it = base + threadIdx.x / lpi, sub = threadIdx.x % lpi;
+      const int m = it >> 5, f = it & 31;
+      const int n = n0g + 4 * f;
+      const bool ok = it < items && n < g.N;
+      float4 a4 = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (ok) {
+        for (int j = sub; j < nsl; j += 4 * lpi) {
+          const float* src[4];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int jj = min(j + u * lpi, nsl - 1);          // past the end: a valid address, value dropped
+            const size_t row = static_cast<size_t>(jj / PLANES) * Mv + m * PLANES + jj % PLANES;
+            src[u] = g.partial + row * g.N + n;
+          }
+          float4 p4[4];
+          load_agent16x4(src[0], src[1], src[2], src[3], p4);
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            if (j + u * lpi < nsl) { a4.x += p4[u].x; a4.y += p4[u].y; a4.z += p4[u].z; a4.w += p4[u].w; }
+        }
+      }
+      red[threadIdx.x] = a4;
+      __syncthreads();
+      float sq = 0.f;
+      if (ok && sub == 0) {
+        float4 sum = g.residual ? *reinterpret_cast<const float4*>(g.residual + static_cast<size_t>(m) * g.N + n)
+                                : make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int u = 0; u < lpi; ++u) {
+          const float4 r4 = red[threadIdx.x + u];
+          sum.x += r4.x; sum.y += r4.y; sum.z += r4.z; sum.w += r4.w;
+        }
+        *reinterpret_cast<float4*>(g.out_x + static_cast<size_t>(m) * g.N + n) = sum;
+        if (g.out_store) {
+          uint2 pk;
+          pk.x = pack_bf16x2(sum.x, sum.y);
+          pk.y = pack_bf16x2(sum.z, sum.w);
+          *reinterpret_cast<uint2*>(static_cast<bf16_t*>(g.out_store) + static_cast<size_t>(m) * g.N + n) = pk;
+        }
+        sq = sum.x * sum.x + sum.y * sum.y + sum.z * sum.z + sum.w * sum.w;
+      }
+      sq_lds[threadIdx.x] = sq;
+      __syncthreads();
+      if (g.out_ssq && it < items && sub == 0 && f == 0) {
+        float tot = 0.f;
+        for (int u = 0; u < 32; ++u) tot += sq_lds[threadIdx.x + u * lpi];
+        g.out_ssq[m * static_cast<int>(gridDim.x) + blockIdx.x] = tot;
+      }
+      __syncthreads();
     }
     return;
   }
@@ -461,6 +586,16 @@ void choose_ksplit(GemmArgs& g, bool mfma) {
   g.kc = kcb * 128;
 }
 
+__global__ void k_zero_i32(int* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+
+hipError_t launch_zero_i32(int* p, int n, hipStream_t s) {
+  hipLaunchKernelGGL(k_zero_i32, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+  return hipGetLastError();
+}
+
 hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
   const dim3 grid((g.N + 3) / 4);
   if (bf16)
@@ -471,7 +606,10 @@ hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
 }
 
 size_t gemm_mfma_lds_bytes(const GemmArgs& g) {
-  return (static_cast<size_t>(g.kc >> 3) * g.M * g.planes + static_cast<size_t>(kGemmWaves) * 256) * 16;
+  // activation pieces, one weight tile per wave, the rows' 1 / rms; the reducing epilogue
+  // overlays 512 float4 + 512 float on the front
+  const size_t main = (static_cast<size_t>(g.kc >> 3) * g.M * g.planes + static_cast<size_t>(kGemmWaves) * 256) * 16;
+  return main + ((static_cast<size_t>(g.M) * sizeof(float) + 15) & ~static_cast<size_t>(15));
 }
 
 template <int MT, int PLANES, bool HEAD>
@@ -479,7 +617,7 @@ static hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   static bool attr_set = false;
   if (!attr_set) {
     const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_mfma<MT, PLANES, HEAD>),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+                                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
     if (e != hipSuccess) return e;
     attr_set = true;
   }

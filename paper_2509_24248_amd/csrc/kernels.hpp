@@ -23,11 +23,28 @@ struct GemmArgs {
   // MFMA path: where the activations come from
   int a_mode;          // 0: fp32 rows [M][K]; 1: bf16 rows [M][K];
                        // 2: bf16 [embed[tok[m]] ; hidden[m]], each K/2 wide (the draft's fuse input)
-  const void* a_src;   // rows (modes 0, 1) or hidden rows (mode 2)
+                       // 3: RMSNorm of fp32 rows: a_src[m][k] * rsqrt(sum_j a_ssq[m][j] / K + a_eps) * a_gain[k]
+                       // 4: silu(gate) * up, gate = columns k, up = columns K + k of the a_nslices
+                       //    partial slices a_src left by a GEMM with N = 2K
+  const void* a_src;   // rows (modes 0, 1, 3), hidden rows (mode 2) or partial sums (mode 4)
+  const float* a_ssq;  // mode 3: [M][a_nssq] pieces of the rows' sums of squares
+  int a_nssq;
+  const void* a_gain;  // mode 3: [K] bf16 norm gain
+  float a_eps;
+  int a_nslices;       // mode 4: ksplit * planes of the producing GEMM
+  int a_src_planes;    //         and its planes
   const void* a_embed; // mode 2: embedding table [V][K/2]
   const int32_t* a_tok;  // mode 2: token ids [M]
   int kc;              // K elements of activations staged in LDS at a time (multiple of 128)
   float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
+  // epi = 1: the workgroup that finishes a 128-row group last adds up the group's partial
+  // sums in a fixed order (+ residual) and writes the finished rows
+  int epi;
+  int* counters;       // [groups], zero before the launch and again after it
+  const float* residual;  // [M][N] or nullptr
+  float* out_x;        // [M][N] fp32
+  void* out_store;     // [M][N] bf16 or nullptr
+  float* out_ssq;      // [M][groups] sum of squares of the group's columns, or nullptr
   int V;               // head mode when >= 0
   int n_extra;
   int top_b;           // head mode: candidates kept per tile (0 or 1 = the argmax only)
@@ -38,6 +55,8 @@ struct GemmArgs {
 };
 
 inline int gemm_ntiles(int N) { return (N + 15) / 16; }
+inline int gemm_groups(int N) { return (gemm_ntiles(N) + 7) / 8; }   // 128-row groups = workgroups along N
+hipError_t launch_zero_i32(int* p, int n, hipStream_t s);
 inline int gemm_mt(int M, int planes) { return (M * planes + 15) / 16; }
 
 bool gemm_mfma_supported(int M, int planes, int K);
