@@ -110,6 +110,7 @@ class Round:
         self.cfg = sx.exit_cfg(stop_think_token=case.stop_think_token)
         ws = lambda n: torch.empty(max(n, 256), dtype=torch.uint8, device="cuda")
         self.ws_draft = ws(sx.specexit_draft_step_workspace_bytes(self.desc, self.dview, B))
+        sx.specexit_workspace_prepare(self.ws_draft)      # kept to the draft step: its counters stay zero
         self.ws_attn = ws(sx.specexit_verify_attn_workspace_bytes(self.tview, B, n_q, shape.Hq))
         self.ws_head = ws(sx.specexit_lmhead_argmax_workspace_bytes(self.code, B * n_q, shape.D, shape.V, 0))
         self.scale = shape.d ** -0.5
@@ -124,7 +125,8 @@ class Round:
         for j in range(self.n_draft_steps):
             hout = self.hid[j & 1]
             sx.specexit_draft_step(self.desc, self.w, self.dview, s.B, tok, hin, self.pos[j], hout,
-                                   self.next_tok[j], self.sig_raw[j], self.sig[j], self.ws_draft)
+                                   self.next_tok[j], self.sig_raw[j], self.sig[j], self.ws_draft,
+                                   flags=sx.FLAG_WORKSPACE_PREPARED)
             tok, hin = self.next_tok[j], hout
         sx.specexit_verify_attn(self.tview, s.B, s.n_q, s.Hq, self.q, self.ctx, self.mask, self.scale,
                                 self.attn_out, self.ws_attn)

@@ -47,6 +47,11 @@ typedef enum { SPECEXIT_KV_CONTIG = 0, SPECEXIT_KV_PAGED = 1 } specexit_kv_layou
 /* Limits: 1 <= n_q <= 64 (one mask bit per block entry); head_dim in {64, 128};
  * n_q_heads % n_kv_heads == 0; (n_q_heads / n_kv_heads) * n_q <= 128;
  * page_size a multiple of 16; hidden, intermediate, n_q_heads*head_dim multiples of 64. */
+/* flags bit: the workspace passed to specexit_draft_step / specexit_draft_tree_level was
+ * zero-filled once (specexit_workspace_prepare) and has since been written only by calls of
+ * that same entry point with the same descriptor, cache view and row counts.  The call then
+ * skips the launch that clears its arrival counters (every kernel leaves them at zero). */
+#define SPECEXIT_FLAG_WORKSPACE_PREPARED 1u
 #define SPECEXIT_MAX_NQ 64
 #define SPECEXIT_MAX_TOP_B 4 /* ranked continuations a tree-drafting row can report */
 #define SPECEXIT_N_SIGNALS 3
@@ -139,6 +144,9 @@ int32_t specexit_draft_step(const specexit_model_desc *desc, const specexit_draf
                             void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 size_t specexit_draft_step_workspace_bytes(const specexit_model_desc *desc,
                                            const specexit_kv_view *draft_kv, int32_t B);
+
+/* Zero-fills a workspace (a small kernel on `stream`; see SPECEXIT_FLAG_WORKSPACE_PREPARED). */
+int32_t specexit_workspace_prepare(void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- stage 1 over a tree: one level of tree drafting (the block "forward through M_t with
  * tree attention" of Alg. 1 verifies; the draft forward is that of specexit_draft_step) ----

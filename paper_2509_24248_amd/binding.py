@@ -25,11 +25,12 @@ EXPORTS = [
     "specexit_verify_attn", "specexit_verify_attn_workspace_bytes",
     "specexit_lmhead_argmax", "specexit_lmhead_argmax_workspace_bytes",
     "specexit_draft_tree_level", "specexit_draft_tree_level_workspace_bytes", "specexit_tree_gather",
-    "specexit_accept_exit", "specexit_kv_compact", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
+    "specexit_workspace_prepare", "specexit_accept_exit", "specexit_kv_compact", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
 SMOOTH_EWMA, SMOOTH_NONE, SMOOTH_WINDOW, SMOOTH_MOMENTUM, SMOOTH_PARAGRAPH = 0, 1, 2, 3, 4
 SMOOTH_WORDS = 48
+FLAG_WORKSPACE_PREPARED = 1
 
 
 class SpecExitError(RuntimeError):
@@ -98,6 +99,8 @@ def _load() -> C.CDLL:
                                               vp, vp, vp, i32, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, sz, u32, vp]
     lib.specexit_tree_gather.restype = i32
     lib.specexit_tree_gather.argtypes = [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
+    lib.specexit_workspace_prepare.restype = i32
+    lib.specexit_workspace_prepare.argtypes = [vp, sz, vp]
     lib.specexit_kv_compact.restype = i32
     lib.specexit_kv_compact.argtypes = [C.POINTER(KVView), i32, C.c_int64, i32, i32, vp, vp, vp, vp, vp, i32, vp, u32, vp]
     lib.specexit_copy_probe.restype = i32
@@ -208,6 +211,11 @@ def specexit_draft_step(desc: ModelDesc, w: DraftWeights, draft_kv: KVView, B: i
     _check(LIB.specexit_draft_step(C.byref(desc), C.byref(w), C.byref(draft_kv), B, _ptr(tok), _ptr(hidden_in),
                                    _ptr(pos), _ptr(hidden_out), _ptr(next_tok), _ptr(sig_raw), _ptr(sig),
                                    wp, wb, flags, _stream(stream)))
+
+
+def specexit_workspace_prepare(workspace, stream=None) -> None:
+    wp, wb = _ws_args(workspace)
+    _check(LIB.specexit_workspace_prepare(wp, wb, _stream(stream)))
 
 
 def specexit_draft_tree_level_workspace_bytes(desc: ModelDesc, draft_kv: KVView, B: int, W: int, top_b: int) -> int:

@@ -255,7 +255,7 @@ DraftBufs carve_draft(const DraftPlan& p, void* ws) {
   b.extra = c.take<float>(sizeof(float) * p.B * 3);
   const int gd = gemm_groups(p.dm.D);
   b.ssq = c.take<float>(sizeof(float) * 3 * p.B * gd);
-  b.n_counters = 3 * gd;
+  b.n_counters = 3 * gd + gemm_groups((p.dm.Hq + 2 * p.dm.Hkv) * p.dm.d);
   b.counters = c.take<int>(sizeof(int) * b.n_counters);
   b.total = c.off;
   return b;
@@ -286,6 +286,7 @@ struct DraftIO {
   int32_t* cand_tok;         // [rows, top_b]
   float* cand_logit;         // [rows, top_b] or null
   float *sig_raw, *sig;      // [rows, 3]
+  uint32_t flags;
 };
 
 int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_kv_view* draft_kv, const DraftIO& io,
@@ -312,7 +313,10 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     // (+ residual) in the workgroup that arrives last, leaving the rows and the pieces of
     // their sums of squares; the next GEMM applies the RMSNorm while it stages its activations,
     // and the down projection applies the SiLU gate the same way.
-    if ((rc = check_hip(launch_zero_i32(b.counters, b.n_counters, s), "zero counters"))) return rc;
+    // the counters must start at zero and every kernel leaves them at zero: a caller that keeps
+    // a zero-filled workspace to this call (same shapes) may say so and save the clearing launch
+    if (!(io.flags & SPECEXIT_FLAG_WORKSPACE_PREPARED))
+      if ((rc = check_hip(launch_zero_i32(b.counters, b.n_counters, s), "zero counters"))) return rc;
     auto reducing = [&](GemmArgs& g, int which, const float* residual, float* out_x, void* out_store) {
       g.epi = 1;
       g.counters = b.counters + which * gd;
@@ -338,6 +342,14 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
     // q, k, v; rotary; cache write; attention over the draft's own cache
     normed(p.qkv, 0, b.x_buf, w->ln_attn);
+    p.qkv.epi = 2;     // finished heads are rotated and stored as q / cache entries by the GEMM itself
+    p.qkv.counters = b.counters + 3 * gd;
+    RopeArgs& ra = p.qkv.rope;
+    ra.pos = io.pos; ra.level = io.level; ra.node = io.node; ra.W = p.W; ra.theta = dm.rope_theta;
+    for (int c = 0; c < dm.d / 2; ++c) ra.inv_freq[c] = pow(static_cast<double>(dm.rope_theta), -2.0 * c / dm.d);
+    ra.Hq = dm.Hq; ra.Hkv = dm.Hkv; ra.d = dm.d; ra.q_out = b.q_buf; ra.paged = p.attn.paged;
+    ra.kc = draft_kv->k; ra.vc = draft_kv->v; ra.page_table = draft_kv->page_table;
+    ra.page_size = p.attn.page_size; ra.max_pages = p.attn.max_pages; ra.l_max = p.attn.l_max;
     if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
   } else {
     if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, io.tok, io.hidden_in, b.act, s), "embed_concat"))) return rc;
@@ -345,10 +357,10 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.fc.ksplit, p.fc.planes, nullptr, w->ln_attn,
                                            b.x_buf, nullptr, b.act, s), "norm attn"))) return rc;
     if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
+    if ((rc = check_hip(launch_rope_kvwrite(dm, B, p.W, b.partial, p.qkv.ksplit, p.qkv.planes, io.pos, io.level, io.node,
+                                            b.q_buf, p.attn.paged, draft_kv->k, draft_kv->v, draft_kv->page_table,
+                                            p.attn.page_size, p.attn.max_pages, p.attn.l_max, s), "rope"))) return rc;
   }
-  if ((rc = check_hip(launch_rope_kvwrite(dm, B, p.W, b.partial, p.qkv.ksplit, p.qkv.planes, io.pos, io.level, io.node,
-                                          b.q_buf, p.attn.paged, draft_kv->k, draft_kv->v, draft_kv->page_table,
-                                          p.attn.page_size, p.attn.max_pages, p.attn.l_max, s), "rope"))) return rc;
   AttnArgs at = p.attn;
   at.q = b.q_buf;
   at.ctx_len = io.pos;
@@ -476,12 +488,12 @@ int32_t specexit_draft_step(const specexit_model_desc* desc, const specexit_draf
                             const void* hidden_in, const int32_t* pos, void* hidden_out, int32_t* next_tok,
                             float* sig_raw, float* sig, void* workspace, size_t workspace_bytes,
                             uint32_t flags, void* stream) {
-  (void)flags;
   DraftPlan p;
   int32_t rc = make_draft_plan(p, desc, draft_kv, B);
   if (rc) return rc;
   DraftIO io;
   memset(&io, 0, sizeof(io));
+  io.flags = flags;
   io.tok = tok; io.hidden_in = hidden_in; io.pos = pos; io.n_blk = 1;
   io.hidden_out = hidden_out; io.cand_tok = next_tok; io.sig_raw = sig_raw; io.sig = sig;
   return run_draft(p, w, draft_kv, io, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
@@ -501,7 +513,6 @@ int32_t specexit_draft_tree_level(const specexit_model_desc* desc, const specexi
                                   void* hidden_out, int32_t* cand_tok, float* cand_logit, float* sig_raw,
                                   float* sig, void* workspace, size_t workspace_bytes, uint32_t flags,
                                   void* stream) {
-  (void)flags;
   DraftPlan p;
   int32_t rc = make_draft_plan(p, desc, draft_kv, B, W, top_b);
   if (rc) return rc;
@@ -511,7 +522,7 @@ int32_t specexit_draft_tree_level(const specexit_model_desc* desc, const specexi
   DraftIO io;
   memset(&io, 0, sizeof(io));
   io.tok = tok; io.hidden_in = hidden_in; io.pos = ctx_len; io.level = level; io.node = node;
-  io.mask = anc_mask; io.n_blk = n_blk;
+  io.mask = anc_mask; io.n_blk = n_blk; io.flags = flags;
   io.hidden_out = hidden_out; io.cand_tok = cand_tok; io.cand_logit = cand_logit; io.sig_raw = sig_raw; io.sig = sig;
   return run_draft(p, w, draft_kv, io, workspace, workspace_bytes, static_cast<hipStream_t>(stream));
 }
@@ -660,6 +671,14 @@ int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_
   a.accept_len = accept_len; a.accept_path = accept_path; a.recover_tok = recover_tok; a.last_node = last_node;
   a.exit_flag = exit_flag; a.new_ctx_len = new_ctx_len;
   return check_hip(launch_accept_exit(a, static_cast<hipStream_t>(stream)), "accept_exit");
+}
+
+int32_t specexit_workspace_prepare(void* workspace, size_t workspace_bytes, void* stream) {
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return fail(SPECEXIT_EWORKSPACE, "workspace_prepare: workspace null or not 256-byte aligned");
+  if (workspace_bytes / 4 > 0x7fffffff) return fail(SPECEXIT_EINVAL, "workspace_prepare: workspace too large");
+  if (workspace_bytes < 4) return SPECEXIT_OK;
+  return check_hip(launch_zero_i32(static_cast<int*>(workspace), static_cast<int>(workspace_bytes / 4),
+                                   static_cast<hipStream_t>(stream)), "workspace_prepare");
 }
 
 int32_t specexit_tree_gather(int32_t dtype, int32_t B, int32_t W_prev, int32_t top_b, int32_t W_next, int32_t D,

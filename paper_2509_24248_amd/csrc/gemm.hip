@@ -218,6 +218,14 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
 #pragma unroll
   for (int t = 0; t < MT; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+  // Split projections run for a few microseconds only: the first block's weights are requested
+  // before the activations are staged, and each further block before the current one is used.
+  constexpr bool PF = !HEAD;
+  uint4 nxt[4];
+  if (PF && active && kb0 < kb1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) nxt[i] = load_stream16(src[i] + (static_cast<size_t>(kb0) << 8));
+  }
   const int kcb = g.kc >> 7;           // 128-element blocks per staged chunk
   for (int c0 = kb0; c0 < kb1; c0 += kcb) {
     const int c1 = min(kb1, c0 + kcb);
@@ -227,8 +235,17 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
     if (!active) continue;
     for (int kb = c0; kb < c1; ++kb) {
       uint4 wr[4];
+      if (PF) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) wr[i] = load_stream16(src[i] + (static_cast<size_t>(kb) << 8));
+        for (int i = 0; i < 4; ++i) wr[i] = nxt[i];
+        if (kb + 1 < kb1) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) nxt[i] = load_stream16(src[i] + (static_cast<size_t>(kb + 1) << 8));
+        }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) wr[i] = load_stream16(src[i] + (static_cast<size_t>(kb) << 8));
+      }
 #pragma unroll
       for (int i = 0; i < 4; ++i) my[(4 * i + (lane >> 4)) * 16 + pos] = wr[i];
       // the tile is private to this wave, whose LDS operations retire in order: a compiler
@@ -298,6 +315,7 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
     if (!s_last) return;
     float4* red = reinterpret_cast<float4*>(dyn_lds);           // the tiles are done with: reuse their LDS
     float* sq_lds = reinterpret_cast<float*>(red + 64 * kGemmWaves);
+    float* xs = sq_lds + 64 * kGemmWaves;                       // epi = 2: the group's finished rows [M][128]
     constexpr int NT = 64 * kGemmWaves;
     const int items = g.M * 32;                                  // float4 outputs of the group
     int lpi = 1;                                                 // threads sharing one output
@@ -336,7 +354,8 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
           const float4 r4 = red[threadIdx.x + u];
           sum.x += r4.x; sum.y += r4.y; sum.z += r4.z; sum.w += r4.w;
         }
-        *reinterpret_cast<float4*>(g.out_x + static_cast<size_t>(m) * g.N + n) = sum;
+        if (g.epi == 2) *reinterpret_cast<float4*>(xs + m * 128 + 4 * f) = sum;
+        else *reinterpret_cast<float4*>(g.out_x + static_cast<size_t>(m) * g.N + n) = sum;
         if (g.out_store) {
           uint2 pk;
           pk.x = pack_bf16x2(sum.x, sum.y);
@@ -353,6 +372,52 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
         g.out_ssq[m * static_cast<int>(gridDim.x) + blockIdx.x] = tot;
       }
       __syncthreads();
+    }
+    if (g.epi == 2) {
+      // the group's 128 columns are whole heads of q, k or v: rotate (pairs c, c + d/2) and store
+      const RopeArgs& ra = g.rope;
+      const int half = ra.d >> 1;
+      const int pairs = g.M * 64;                               // (row, pair) items of the group
+      for (int idx = threadIdx.x; idx < pairs; idx += NT) {
+        const int m = idx >> 6, pr = idx & 63;
+        const int hl = pr / half, c = pr - hl * half;           // head inside the group, pair inside the head
+        const int hh = n0g / ra.d + hl;                         // head among q heads, then k heads, then v heads
+        if (hh >= ra.Hq + 2 * ra.Hkv) continue;
+        float x1 = xs[m * 128 + hl * ra.d + c], x2 = xs[m * 128 + hl * ra.d + c + half];
+        const int b = m / ra.W;
+        const int ps = ra.pos[b] + ra.level;
+        const int slot = ra.pos[b] + (ra.node ? ra.node[m % ra.W] : 0);
+        if (hh < ra.Hq + ra.Hkv) {
+          // angle in double (long positions keep their phase), reduced to [-pi, pi] in double,
+          // sine and cosine of the remainder in float
+          const double ang = static_cast<double>(ps) * ra.inv_freq[c];
+          const double turns = rint(ang * 0.15915494309189535);
+          const float red_ang = static_cast<float>(fma(-turns, 6.283185307179586, ang));
+          const float cs = cosf(red_ang), sn = sinf(red_ang);
+          const float r1 = x1 * cs - x2 * sn;
+          const float r2 = x2 * cs + x1 * sn;
+          x1 = r1;
+          x2 = r2;
+        }
+        bf16_t* dst;
+        if (hh < ra.Hq) {
+          dst = static_cast<bf16_t*>(ra.q_out) + (static_cast<size_t>(m) * ra.Hq + hh) * ra.d;
+        } else {
+          if (slot < 0 || slot >= ra.l_max) continue;           // an entry outside the cache is not written
+          const bool is_k = hh < ra.Hq + ra.Hkv;
+          const int h = is_k ? hh - ra.Hq : hh - ra.Hq - ra.Hkv;
+          size_t off;
+          if (ra.paged) {
+            const int page = ra.page_table[static_cast<size_t>(b) * ra.max_pages + slot / ra.page_size];
+            off = ((static_cast<size_t>(page) * ra.Hkv + h) * ra.page_size + slot % ra.page_size) * ra.d;
+          } else {
+            off = ((static_cast<size_t>(b) * ra.Hkv + h) * ra.l_max + slot) * ra.d;
+          }
+          dst = static_cast<bf16_t*>(is_k ? ra.kc : ra.vc) + off;
+        }
+        dst[c] = f32_to_bf16(x1);
+        dst[c + half] = f32_to_bf16(x2);
+      }
     }
     return;
   }
@@ -569,7 +634,8 @@ void choose_ksplit(GemmArgs& g, bool mfma) {
     g.ksplit = 1;
     g.kb_per_split = KB;
   } else {
-    // enough (tile, K range) units to give every SIMD a few waves
+    // enough (tile, K range) units to give every SIMD a few waves; more and shorter ranges
+    // were measured slower (staging and the reduction are paid per workgroup)
     const int ntiles = gemm_ntiles(g.N);
     int want = (2048 + ntiles - 1) / ntiles;
     if (want < 1) want = 1;
@@ -608,8 +674,10 @@ hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
 size_t gemm_mfma_lds_bytes(const GemmArgs& g) {
   // activation pieces, one weight tile per wave, the rows' 1 / rms; the reducing epilogue
   // overlays 512 float4 + 512 float on the front
-  const size_t main = (static_cast<size_t>(g.kc >> 3) * g.M * g.planes + static_cast<size_t>(kGemmWaves) * 256) * 16;
-  return main + ((static_cast<size_t>(g.M) * sizeof(float) + 15) & ~static_cast<size_t>(15));
+  const size_t main = (static_cast<size_t>(g.kc >> 3) * g.M * g.planes + static_cast<size_t>(kGemmWaves) * 256) * 16 +
+                      ((static_cast<size_t>(g.M) * sizeof(float) + 15) & ~static_cast<size_t>(15));
+  const size_t overlay = g.epi == 0 ? 0 : static_cast<size_t>(64 * kGemmWaves) * 20 + (g.epi == 2 ? static_cast<size_t>(g.M) * 512 : 0);
+  return main > overlay ? main : overlay;
 }
 
 template <int MT, int PLANES, bool HEAD>

@@ -11,6 +11,25 @@ namespace sx {
 // partial sums  partial[ks][v][n]  with v = m * planes + plane: consumers add the
 // ksplit * planes slices.  In head mode (V >= 0) rows n < V enter a fused argmax and
 // rows V.. are the signal rows of the widened head.
+// Rotary embedding + cache write done by the q/k/v projection's reducing epilogue (epi = 2):
+// row r of the step is sequence r / W, rotary position pos[r / W] + level, cache entry
+// pos[r / W] + node[r % W] (node null: the entry at pos).
+struct RopeArgs {
+  const int32_t* pos;
+  int level;
+  const int32_t* node;
+  int W;
+  float theta;
+  double inv_freq[64];       // theta^(-2c/d) for c < d/2, filled on the host
+  int Hq, Hkv, d;
+  void* q_out;               // [rows][Hq][d] bf16
+  int paged;
+  void *kc, *vc;
+  const int32_t* page_table;
+  int page_size, max_pages;
+  int64_t l_max;
+};
+
 struct GemmArgs {
   const void* w[3];
   int seg_end[3];      // exclusive end row of each block in the concatenated row space
@@ -45,6 +64,7 @@ struct GemmArgs {
   float* out_x;        // [M][N] fp32
   void* out_store;     // [M][N] bf16 or nullptr
   float* out_ssq;      // [M][groups] sum of squares of the group's columns, or nullptr
+  RopeArgs rope;       // epi = 2: the finished rows are q / k / v heads (bf16 outputs)
   int V;               // head mode when >= 0
   int n_extra;
   int top_b;           // head mode: candidates kept per tile (0 or 1 = the argmax only)

@@ -125,7 +125,7 @@ class GpuDraft:
         self.ws = workspace(lib.specexit_draft_step_workspace_bytes(self.desc, self.view, shape.B))
         assert self.ws.numel() > 256, lib.last_error()
 
-    def step(self, tok, hidden_in, pos):
+    def step(self, tok, hidden_in, pos, flags=0):
         shape, B = self.shape, self.shape.B
         hin = dev(hidden_in, shape)
         hout = torch.empty_like(hin)
@@ -133,7 +133,7 @@ class GpuDraft:
         sr = torch.empty((B, 3), dtype=torch.float32, device="cuda")
         sg = torch.empty((B, 3), dtype=torch.float32, device="cuda")
         self.lib.specexit_draft_step(self.desc, self.w, self.view, B, dev(tok.astype(np.int32)), hin,
-                                     dev(pos.astype(np.int32)), hout, nt, sr, sg, self.ws)
+                                     dev(pos.astype(np.int32)), hout, nt, sr, sg, self.ws, flags=flags)
         torch.cuda.synchronize()
         return {"hidden_out": host(hout), "next_tok": host(nt), "sig_raw": host(sr), "sig": host(sg)}
 

@@ -96,3 +96,20 @@ def test_full_size_config_1():
     w, kv, tok, g, pos = setup(shape, 0, norms=False)
     w = force_draft_gap(shape, w, kv, tok, g, pos)
     one_step(shape, w, kv, tok, g, pos, label="config 1 full size")
+
+
+def test_prepared_workspace_flag_gives_the_same_results_call_after_call():
+    """With the workspace zero-filled once and the flag set, the call skips clearing its
+    arrival counters; every kernel must leave them at zero for the next call."""
+    shape = gen.scaled(gen.config(2), D=512, Hq=8, Hkv=2, d=128, I=1024, V=5000, B=3, ctx=(10, 400), k=2)
+    w, kv, tok, g, pos = setup(shape, 7, std=0.05)
+    w = force_draft_gap(shape, w, kv, tok, g, pos)
+    plain = GpuDraft(shape, w, kv)
+    prep = GpuDraft(shape, w, kv)
+    prep.ws.fill_(0x5A)                                   # garbage first: prepare must clear it
+    prep.lib.specexit_workspace_prepare(prep.ws)
+    for it in range(4):
+        a = plain.step(tok, g, pos + it)
+        b = prep.step(tok, g, pos + it, flags=prep.lib.FLAG_WORKSPACE_PREPARED)
+        for k in a:
+            np.testing.assert_array_equal(a[k], b[k], err_msg=f"call {it} {k}")
