@@ -167,55 +167,81 @@ __global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
   }
 }
 
-// Merge the chunks of one (sequence, query, head): exact log-sum-exp combination.  One wave
-// per output row; the chunk maxima are scanned lane-parallel, the partial outputs are
-// accumulated four chunks at a time so that their loads overlap.
+// Merge the chunks of one (sequence, query, head): exact log-sum-exp combination.  One
+// workgroup per output row: the chunks' weights exp(m_s - max) are formed once in LDS, then
+// the threads split into groups that each take every NG-th chunk of one float4 column, so
+// all partial outputs are requested at once; the groups are added in a fixed order.
+constexpr int kCombThreads = 256;
+
 template <typename T, int D>
-__global__ __launch_bounds__(64) void k_attn_combine(const AttnArgs a) {
-  constexpr int PER = D / 64;   // output columns per lane
+__global__ __launch_bounds__(kCombThreads) void k_attn_combine(const AttnArgs a) {
+  constexpr int C4 = D / 4;                 // float4 columns of a row
+  constexpr int NG = kCombThreads / C4;     // chunk groups
+  extern __shared__ float w_lds[];          // [nsplit] weights, then NG x C4 float4 for the group sums
+  __shared__ float red[kCombThreads / 64];
   const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
-  const int lane = threadIdx.x;
   const int G = a.Hq / a.Hkv;
   const int R = G * a.n_q;
   const int g = h / G, r = i * G + h % G;
   const int total = a.ctx_len[b] + a.n_blk;
-  const int nact = (total + a.chunk - 1) / a.chunk;
+  const int nact = min((total + a.chunk - 1) / a.chunk, a.nsplit);
   const size_t unit0 = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit;
   const float* ml = a.part_ml + (unit0 * R + r) * 2;          // chunk s at ml[s * R * 2]
-  const float* po = a.part_o + (unit0 * R + r) * D + lane * PER;  // chunk s at po[s * R * D]
-  float mmax = -INFINITY;
-  for (int s = lane; s < nact; s += 64) mmax = fmaxf(mmax, ml[static_cast<size_t>(s) * R * 2]);
-  mmax = wave_max(mmax);
-  float den = 0.f;
-  for (int s = lane; s < nact; s += 64) {
-    const float ms = ml[static_cast<size_t>(s) * R * 2];
-    if (ms != -INFINITY) {
-      const float w = a.use_mfma ? exp2f(ms - mmax) : expf(ms - mmax);
-      den = fmaf(w, ml[static_cast<size_t>(s) * R * 2 + 1], den);
-    }
-  }
-  den = wave_sum(den);
-  float num[PER];
+  const float* po = a.part_o + (unit0 * R + r) * D;            // chunk s at po[s * R * D]
+  float mloc = -INFINITY;
+  for (int s = threadIdx.x; s < nact; s += kCombThreads) mloc = fmaxf(mloc, ml[static_cast<size_t>(s) * R * 2]);
+  mloc = wave_max(mloc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = mloc;
+  __syncthreads();
+  float mmax = red[0];
 #pragma unroll
-  for (int e = 0; e < PER; ++e) num[e] = 0.f;
-  for (int s = 0; s < nact; s += 4) {
-    float w[4], o[4][PER];
+  for (int w = 1; w < kCombThreads / 64; ++w) mmax = fmaxf(mmax, red[w]);
+  __syncthreads();
+  float dloc = 0.f;
+  for (int s = threadIdx.x; s < nact; s += kCombThreads) {
+    const float ms = ml[static_cast<size_t>(s) * R * 2];
+    float w = 0.f;
+    if (ms != -INFINITY) w = a.use_mfma ? exp2f(ms - mmax) : expf(ms - mmax);
+    w_lds[s] = w;
+    dloc = fmaf(w, w != 0.f ? ml[static_cast<size_t>(s) * R * 2 + 1] : 0.f, dloc);
+  }
+  dloc = wave_sum(dloc);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = dloc;
+  __syncthreads();
+  float den = 0.f;
+#pragma unroll
+  for (int w = 0; w < kCombThreads / 64; ++w) den += red[w];
+  const int sg = threadIdx.x / C4, c4 = threadIdx.x % C4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s = sg; s < nact; s += 4 * NG) {
+    float4 o[4];
+    float w[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int ss = min(s + u, nact - 1);
-      const float ms = ml[static_cast<size_t>(ss) * R * 2];
-      w[u] = (s + u < nact && ms != -INFINITY) ? (a.use_mfma ? exp2f(ms - mmax) : expf(ms - mmax)) : 0.f;
-#pragma unroll
-      for (int e = 0; e < PER; ++e) o[u][e] = po[static_cast<size_t>(ss) * R * D + e];
+      const int ss = min(s + u * NG, nact - 1);
+      w[u] = s + u * NG < nact ? w_lds[ss] : 0.f;
+      o[u] = *reinterpret_cast<const float4*>(po + static_cast<size_t>(ss) * R * D + c4 * 4);
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u)
-#pragma unroll
-      for (int e = 0; e < PER; ++e) num[e] = fmaf(w[u], w[u] != 0.f ? o[u][e] : 0.f, num[e]);
+      if (w[u] != 0.f) {
+        acc.x = fmaf(w[u], o[u].x, acc.x); acc.y = fmaf(w[u], o[u].y, acc.y);
+        acc.z = fmaf(w[u], o[u].z, acc.z); acc.w = fmaf(w[u], o[u].w, acc.w);
+      }
   }
-  T* dst = static_cast<T*>(a.out) + ((static_cast<size_t>(b) * a.n_q + i) * a.Hq + h) * D + lane * PER;
-#pragma unroll
-  for (int e = 0; e < PER; ++e) Elem<T>::store(dst + e, num[e] / den);
+  float4* gs = reinterpret_cast<float4*>(w_lds + ((a.nsplit + 3) & ~3));
+  gs[sg * C4 + c4] = acc;
+  __syncthreads();
+  if (sg == 0) {
+    float4 sum = gs[c4];
+    for (int u = 1; u < NG; ++u) {
+      const float4 v = gs[u * C4 + c4];
+      sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    }
+    T* dst = static_cast<T*>(a.out) + ((static_cast<size_t>(b) * a.n_q + i) * a.Hq + h) * D + c4 * 4;
+    Elem<T>::store(dst + 0, sum.x / den); Elem<T>::store(dst + 1, sum.y / den);
+    Elem<T>::store(dst + 2, sum.z / den); Elem<T>::store(dst + 3, sum.w / den);
+  }
 }
 
 size_t valu_smem_bytes(const AttnArgs& a) {
@@ -286,12 +312,14 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t s, KernelHook hook, int ho
   if (hook) hook(hook_id, 1, s);
   if (e != hipSuccess) return e;
   const dim3 grid(a.Hq, a.n_q, a.B);
+  const size_t lds = (static_cast<size_t>((a.nsplit + 3) & ~3) + kCombThreads * 4) * sizeof(float);
+  if (lds > 60 * 1024) return hipErrorInvalidValue;
   if (a.dtype == 1) {
-    if (a.d == 128) hipLaunchKernelGGL((k_attn_combine<bf16_t, 128>), grid, dim3(64), 0, s, a);
-    else hipLaunchKernelGGL((k_attn_combine<bf16_t, 64>), grid, dim3(64), 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((k_attn_combine<bf16_t, 128>), grid, dim3(kCombThreads), lds, s, a);
+    else hipLaunchKernelGGL((k_attn_combine<bf16_t, 64>), grid, dim3(kCombThreads), lds, s, a);
   } else {
-    if (a.d == 128) hipLaunchKernelGGL((k_attn_combine<float, 128>), grid, dim3(64), 0, s, a);
-    else hipLaunchKernelGGL((k_attn_combine<float, 64>), grid, dim3(64), 0, s, a);
+    if (a.d == 128) hipLaunchKernelGGL((k_attn_combine<float, 128>), grid, dim3(kCombThreads), lds, s, a);
+    else hipLaunchKernelGGL((k_attn_combine<float, 64>), grid, dim3(kCombThreads), lds, s, a);
   }
   return hipGetLastError();
 }
