@@ -144,6 +144,8 @@ struct DraftPlan {
   int top_b;    // continuations reported per row
   int Kmax;
   GemmArgs fc, qkv, o, gu, down, head;
+  bool gemv;         // few rows: the layer's projections run as row-streaming GEMVs
+  GemvArgs vfc, vqkv, vo, vgu, vdown;
   AttnArgs attn;
   size_t partial_bytes;
   int ntiles_head;
@@ -206,6 +208,28 @@ int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specex
   p.gu.seg_end[0] = I;
   p.gu.seg_end[1] = p.gu.seg_end[2] = 2 * I;
   plan_gemm(p.down, D, I, B, 2, p.mfma, -1);
+  p.gemv = p.mfma && gemv_supported(B, D, 2 * D) && gemv_supported(B, (dm.Hq + 2 * dm.Hkv) * dm.d, D) &&
+           gemv_supported(B, D, Hd) && gemv_supported(B, 2 * I, D) && gemv_supported(B, D, I) && (dm.d % 2) == 0;
+  if (p.gemv) {
+    auto plan_v = [&](GemvArgs& g, int N, int K) {
+      memset(&g, 0, sizeof(g));
+      g.N = N; g.K = K; g.M = B; g.nseg = 1;
+      g.seg_end[0] = g.seg_end[1] = g.seg_end[2] = N;
+      gemv_plan(g, num_cus());
+    };
+    plan_v(p.vfc, D, 2 * D);
+    plan_v(p.vqkv, (dm.Hq + 2 * dm.Hkv) * dm.d, D);
+    p.vqkv.nseg = 3;
+    p.vqkv.seg_end[0] = Hd;
+    p.vqkv.seg_end[1] = Hd + dm.Hkv * dm.d;
+    p.vqkv.seg_end[2] = Hd + 2 * dm.Hkv * dm.d;
+    plan_v(p.vo, D, Hd);
+    plan_v(p.vgu, 2 * I, D);
+    p.vgu.nseg = 2;
+    p.vgu.seg_end[0] = I;
+    p.vgu.seg_end[1] = p.vgu.seg_end[2] = 2 * I;
+    plan_v(p.vdown, D, I);
+  }
   plan_gemm(p.head, dm.V + 3, D, B, 2, p.mfma, dm.V);
   p.head.n_extra = 3;
   p.head.top_b = top_b;
@@ -253,7 +277,7 @@ DraftBufs carve_draft(const DraftPlan& p, void* ws) {
   b.part_idx = c.take<int>(sizeof(int) * p.B * p.ntiles_head * p.top_b);
   b.head_am = c.take<int32_t>(sizeof(int32_t) * p.B);
   b.extra = c.take<float>(sizeof(float) * p.B * 3);
-  const int gd = gemm_groups(p.dm.D);
+  const int gd = p.gemv ? 3 * num_cus() : gemm_groups(p.dm.D);   // pieces per row: GEMV workgroups or 128-row groups
   b.ssq = c.take<float>(sizeof(float) * 3 * p.B * gd);
   b.n_counters = 3 * gd + gemm_groups((p.dm.Hq + 2 * p.dm.Hkv) * p.dm.d);
   b.counters = c.take<int>(sizeof(int) * b.n_counters);
@@ -308,7 +332,33 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
   const bool mf = p.mfma;
 
   const int gd = gemm_groups(dm.D);
-  if (mf) {
+  if (p.gemv) {
+    // Few rows: every projection is a row-streaming GEMV whose epilogue finishes the job
+    // (residual, rotary embedding + cache write, SiLU gate); the RMSNorms are applied while
+    // the next projection stages its activations.
+    const int piece = 3 * num_cus();
+    auto ssq_of = [&](int which) { return b.ssq + static_cast<size_t>(which) * B * piece; };
+    auto normed = [&](GemvArgs& g, int which, const GemvArgs& producer, const float* x, const void* gain) {
+      g.a_mode = 3; g.a_src = x; g.a_ssq = ssq_of(which); g.a_nssq = producer.grid; g.a_gain = gain; g.a_eps = dm.rms_eps;
+    };
+    GemvArgs g = p.vfc;                       // x = W_fc [embed[tok] ; hidden_in]
+    g.w[0] = w->w_fc; g.a_mode = 2; g.a_src = io.hidden_in; g.a_embed = w->embed; g.a_tok = io.tok;
+    g.out_x = b.x_buf; g.out_ssq = ssq_of(0);
+    if ((rc = check_hip(launch_gemv(g, s), "gemv fc"))) return rc;
+    g = p.vqkv;                               // q, k, v with rotary embedding, cache write
+    g.w[0] = w->w_q; g.w[1] = w->w_k; g.w[2] = w->w_v;
+    normed(g, 0, p.vfc, b.x_buf, w->ln_attn);
+    g.epi = 1;
+    {
+      RopeArgs& ra = g.rope;
+      ra.pos = io.pos; ra.level = io.level; ra.node = io.node; ra.W = p.W; ra.theta = dm.rope_theta;
+      for (int c = 0; c < dm.d / 2; ++c) ra.inv_freq[c] = pow(static_cast<double>(dm.rope_theta), -2.0 * c / dm.d);
+      ra.Hq = dm.Hq; ra.Hkv = dm.Hkv; ra.d = dm.d; ra.q_out = b.q_buf; ra.paged = p.attn.paged;
+      ra.kc = draft_kv->k; ra.vc = draft_kv->v; ra.page_table = draft_kv->page_table;
+      ra.page_size = p.attn.page_size; ra.max_pages = p.attn.max_pages; ra.l_max = p.attn.l_max;
+    }
+    if ((rc = check_hip(launch_gemv(g, s), "gemv qkv"))) return rc;
+  } else if (mf) {
     // Fused form: each projection back into the hidden size finishes its own split-K sums
     // (+ residual) in the workgroup that arrives last, leaving the rows and the pieces of
     // their sums of squares; the next GEMM applies the RMSNorm while it stages its activations,
@@ -377,7 +427,29 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     at.part_ml = c.take<float>(units * R * 2 * sizeof(float));
   }
   if ((rc = check_hip(launch_attn(at, s, &g_prof_hook, SPECEXIT_PROF_DRAFT_ATTN), "draft attention"))) return rc;
-  if (mf) {
+  if (p.gemv) {
+    const int piece = 3 * num_cus();
+    auto ssq_of = [&](int which) { return b.ssq + static_cast<size_t>(which) * B * piece; };
+    GemvArgs g = p.vo;                        // a = x + W_o attn
+    g.w[0] = w->w_o; g.a_mode = 1; g.a_src = b.attn_out;
+    g.residual = b.x_buf; g.out_x = b.a_buf; g.out_ssq = ssq_of(1);
+    if ((rc = check_hip(launch_gemv(g, s), "gemv o"))) return rc;
+    g = p.vgu;                                // silu(W_gate m) * (W_up m), m = RMSNorm(a)
+    g.w[0] = w->w_gate; g.w[1] = w->w_up;
+    g.a_mode = 3; g.a_src = b.a_buf; g.a_ssq = ssq_of(1); g.a_nssq = p.vo.grid; g.a_gain = w->ln_mlp; g.a_eps = dm.rms_eps;
+    g.epi = 2; g.out_x = b.act;
+    if ((rc = check_hip(launch_gemv(g, s), "gemv gate/up"))) return rc;
+    g = p.vdown;                              // y = a + W_down (...)
+    g.w[0] = w->w_down; g.a_mode = 0; g.a_src = b.act;
+    g.residual = b.a_buf; g.out_x = b.x_buf; g.out_store = io.hidden_out; g.out_ssq = ssq_of(2);
+    if ((rc = check_hip(launch_gemv(g, s), "gemv down"))) return rc;
+    p.head.a_mode = 3;
+    p.head.a_src = b.x_buf;
+    p.head.a_ssq = ssq_of(2);
+    p.head.a_nssq = p.vdown.grid;
+    p.head.a_gain = w->ln_final;
+    p.head.a_eps = dm.rms_eps;
+  } else if (mf) {
     // a = x + W_o attn
     p.o.a_mode = 1;    // attention output is read in its storage type
     p.o.a_src = b.attn_out;

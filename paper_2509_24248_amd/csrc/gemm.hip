@@ -183,10 +183,12 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
   uint4* w_lds = dyn_lds + (g.kc >> 3) * Mv;
   float* rs_lds = reinterpret_cast<float*>(w_lds + kGemmWaves * 256);   // [M] 1 / rms of the rows (a_mode 3)
   if (g.a_mode == 3) {
-    for (int m = threadIdx.x; m < g.M; m += 64 * kGemmWaves) {
+    // one wave per row: lanes take the pieces in turn, then a fixed-order butterfly
+    for (int m = threadIdx.x >> 6; m < g.M; m += kGemmWaves) {
       float ssq = 0.f;
-      for (int j = 0; j < g.a_nssq; ++j) ssq += g.a_ssq[m * g.a_nssq + j];
-      rs_lds[m] = 1.0f / sqrtf(ssq / static_cast<float>(g.K) + g.a_eps);
+      for (int j = threadIdx.x & 63; j < g.a_nssq; j += 64) ssq += g.a_ssq[m * g.a_nssq + j];
+      ssq = wave_sum(ssq);
+      if ((threadIdx.x & 63) == 0) rs_lds[m] = 1.0f / sqrtf(ssq / static_cast<float>(g.K) + g.a_eps);
     }
     __syncthreads();
   }

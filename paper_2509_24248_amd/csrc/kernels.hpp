@@ -74,6 +74,36 @@ struct GemmArgs {
   float* logits_dbg;   // [M][V] or nullptr
 };
 
+// Row-streaming GEMV for steps of at most four rows (gemv.hip): no split over K, the
+// epilogue runs in the wave that owns a pair of weight rows.
+struct GemvArgs {
+  const void* w[3];
+  int seg_end[3];
+  int nseg;
+  int N, K, M;
+  int a_mode;            // as GemmArgs: 0 fp32 rows, 1 bf16 rows, 2 [embed[tok] ; hidden], 3 RMSNorm of fp32 rows
+  const void* a_src;
+  const void* a_embed;
+  const int32_t* a_tok;
+  const float* a_ssq;
+  int a_nssq;
+  const void* a_gain;
+  float a_eps;
+  int epi;               // 0: rows (2p, 2p+1) -> residual add, out_x / out_store / out_ssq
+                         // 1: rotary pairs of the q|k|v projection -> q_out / cache entries
+                         // 2: (gate p, up p) of the gate|up projection -> out_x[m][p] = silu(gate) * up
+  const float* residual;
+  float* out_x;
+  void* out_store;
+  float* out_ssq;        // [M][grid]
+  RopeArgs rope;
+  int grid, waves;       // launch shape, from gemv_plan
+};
+bool gemv_supported(int M, int N, int K);
+size_t gemv_lds_bytes(const GemvArgs& g);
+void gemv_plan(GemvArgs& g, int num_cus);
+hipError_t launch_gemv(const GemvArgs& g, hipStream_t s);
+
 inline int gemm_ntiles(int N) { return (N + 15) / 16; }
 inline int gemm_groups(int N) { return (gemm_ntiles(N) + 7) / 8; }   // 128-row groups = workgroups along N
 hipError_t launch_zero_i32(int* p, int n, hipStream_t s);
