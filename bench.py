@@ -269,6 +269,33 @@ def main():
             graph_ms = None
     ms = graph_ms if graph_ms is not None else eager_ms
 
+    # ---- time per call of each export (back-to-back calls of one export, outside the timed region)
+    def per_call(fn, n=20):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        torch.cuda.synchronize()
+        a.record(stream)
+        for _ in range(n):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+    s_ = rnd.shape
+    calls = {
+        "specexit_draft_step": per_call(lambda: sx.specexit_draft_step(
+            rnd.desc, rnd.w, rnd.dview, s_.B, rnd.tok0, rnd.g0, rnd.pos[0], rnd.hid[0], rnd.next_tok[0], rnd.sig_raw[0],
+            rnd.sig[0], rnd.ws_draft, flags=sx.FLAG_WORKSPACE_PREPARED)),
+        "specexit_verify_attn": per_call(lambda: sx.specexit_verify_attn(
+            rnd.tview, s_.B, s_.n_q, s_.Hq, rnd.q, rnd.ctx, rnd.mask, rnd.scale, rnd.attn_out, rnd.ws_attn)),
+        "specexit_lmhead_argmax": per_call(lambda: sx.specexit_lmhead_argmax(
+            rnd.code, s_.B * s_.n_q, s_.D, s_.V, 0, rnd.block_hidden, rnd.lm, rnd.target_argmax, workspace=rnd.ws_head)),
+        "specexit_accept_exit": per_call(lambda: sx.specexit_accept_exit(
+            rnd.cfg, s_.B, s_.n_q, rnd.block_tok, rnd.parent, rnd.target_argmax, rnd.sig[0], rnd.ctx, rnd.split, rnd.S,
+            rnd.ewma, rnd.n_obs, rnd.thinking, None, rnd.accept_len, rnd.accept_path, rnd.recover, rnd.last_node,
+            rnd.exit_flag, rnd.new_ctx)),
+    }
+    n_layers = {"tiny_f32": 4, "qwen3_4b_chain": 36, "qwen3_8b_paged": 36, "tree_8b": 36, "qwen3_32b_paged": 64}[shape.name]
+
     e = 2 if shape.dtype == "bf16" else 4
     head_bytes = e * (shape.V + 3) * shape.D + e * 2 * shape.B * shape.D + 8 * shape.B * ((shape.V + 18) // 16)
     lm_bytes = e * shape.V * shape.D + e * shape.B * shape.n_q * shape.D
@@ -294,6 +321,10 @@ def main():
         "other_kernels": {
             "lmhead_gemm": {"avg_launch_ms": lm_ms, "achieved_GBs": lm_bytes / (lm_ms * 1e-3) / 1e9, "bytes": lm_bytes},
             "verify_attn_split": {"avg_launch_ms": attn_ms, "achieved_GBs": kv_bytes / (attn_ms * 1e-3) / 1e9, "bytes": kv_bytes}},
+        "eager_ms_per_call": calls,
+        "projection": {"what": "verify attention call time x target layers (the round above holds one target layer's attention "
+                               "and no target MLP / projection GEMMs)", "n_layers": n_layers,
+                       "verify_attn_ms_all_layers": calls["specexit_verify_attn"] * n_layers},
     }
     if want_cpu:
         sec = cpu_baseline(rnd)

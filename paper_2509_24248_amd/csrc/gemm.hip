@@ -92,6 +92,7 @@ __global__ __launch_bounds__(256) void k_gemv_valu(const GemmArgs g) {
 
 // ------------------------------------------------------------------------- MFMA path
 constexpr int kGemmWaves = 8;   // waves per workgroup, one 16-row weight tile each
+constexpr int kHeadWaves = 8;    // head-mode kernels (4 and 16 waves per workgroup were measured slower)
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -173,7 +174,8 @@ __device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_ld
 }
 
 template <int MT, int PLANES, bool HEAD>
-__global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g) {
+__global__ __launch_bounds__(64 * (HEAD ? kHeadWaves : kGemmWaves)) void k_gemm_mfma(const GemmArgs g) {
+  constexpr int NW = HEAD ? kHeadWaves : kGemmWaves;
   // LDS: [activation pieces of one K chunk][per wave: one 16-row x 128-k weight tile, 4 KB]
   // weight tile entry [row][pos] holds the 16-byte piece (pos ^ row) of that row, so both the
   // coalesced writes and the per-row operand reads touch 16 distinct 16-byte slots
@@ -181,10 +183,10 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
   const int Mv = g.M * PLANES;
   uint4* a_lds = dyn_lds;
   uint4* w_lds = dyn_lds + (g.kc >> 3) * Mv;
-  float* rs_lds = reinterpret_cast<float*>(w_lds + kGemmWaves * 256);   // [M] 1 / rms of the rows (a_mode 3)
+  float* rs_lds = reinterpret_cast<float*>(w_lds + NW * 256);   // [M] 1 / rms of the rows (a_mode 3)
   if (g.a_mode == 3) {
     // one wave per row: lanes take the pieces in turn, then a fixed-order butterfly
-    for (int m = threadIdx.x >> 6; m < g.M; m += kGemmWaves) {
+    for (int m = threadIdx.x >> 6; m < g.M; m += NW) {
       float ssq = 0.f;
       for (int j = threadIdx.x & 63; j < g.a_nssq; j += 64) ssq += g.a_ssq[m * g.a_nssq + j];
       ssq = wave_sum(ssq);
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
   const int lane = threadIdx.x & 63;
   const int wv = threadIdx.x >> 6;
   const int ntiles = (g.N + 15) >> 4;
-  const int tile = blockIdx.x * kGemmWaves + wv;
+  const int tile = blockIdx.x * NW + wv;
   const bool active = tile < ntiles;   // idle waves still take part in the barriers
   const int ks = blockIdx.y;
   const int KB = g.K >> 7;
@@ -232,7 +234,7 @@ __global__ __launch_bounds__(64 * kGemmWaves) void k_gemm_mfma(const GemmArgs g)
   for (int c0 = kb0; c0 < kb1; c0 += kcb) {
     const int c1 = min(kb1, c0 + kcb);
     if (c0 != kb0) __syncthreads();    // everyone is done with the previous chunk
-    stage_activations<PLANES>(g, a_lds, rs_lds, c0 << 7, (c1 - c0) << 7, 64 * kGemmWaves);
+    stage_activations<PLANES>(g, a_lds, rs_lds, c0 << 7, (c1 - c0) << 7, 64 * NW);
     __syncthreads();
     if (!active) continue;
     for (int kb = c0; kb < c1; ++kb) {
@@ -676,7 +678,7 @@ hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
 size_t gemm_mfma_lds_bytes(const GemmArgs& g) {
   // activation pieces, one weight tile per wave, the rows' 1 / rms; the reducing epilogue
   // overlays 512 float4 + 512 float on the front
-  const size_t main = (static_cast<size_t>(g.kc >> 3) * g.M * g.planes + static_cast<size_t>(kGemmWaves) * 256) * 16 +
+  const size_t main = (static_cast<size_t>(g.kc >> 3) * g.M * g.planes + static_cast<size_t>(g.V >= 0 ? kHeadWaves : kGemmWaves) * 256) * 16 +
                       ((static_cast<size_t>(g.M) * sizeof(float) + 15) & ~static_cast<size_t>(15));
   const size_t overlay = g.epi == 0 ? 0 : static_cast<size_t>(64 * kGemmWaves) * 20 + (g.epi == 2 ? static_cast<size_t>(g.M) * 512 : 0);
   return main > overlay ? main : overlay;
@@ -691,8 +693,9 @@ static hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  const dim3 grid((gemm_ntiles(g.N) + kGemmWaves - 1) / kGemmWaves, g.ksplit);
-  hipLaunchKernelGGL((k_gemm_mfma<MT, PLANES, HEAD>), grid, dim3(64 * kGemmWaves), gemm_mfma_lds_bytes(g), s, g);
+  constexpr int NW = HEAD ? kHeadWaves : kGemmWaves;
+  const dim3 grid((gemm_ntiles(g.N) + NW - 1) / NW, g.ksplit);
+  hipLaunchKernelGGL((k_gemm_mfma<MT, PLANES, HEAD>), grid, dim3(64 * NW), gemm_mfma_lds_bytes(g), s, g);
   return hipGetLastError();
 }
 
