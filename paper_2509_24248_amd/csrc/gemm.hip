@@ -648,9 +648,12 @@ void choose_ksplit(GemmArgs& g, bool mfma) {
     g.kb_per_split = (KB + want - 1) / want;
     g.ksplit = (KB + g.kb_per_split - 1) / g.kb_per_split;
   }
-  // activations staged in LDS per chunk: whole K range if it fits in 64 KB
+  // activations staged in LDS per chunk: the whole K range if it fits the budget
   const int Mv = g.M * g.planes;
-  int kcb = (64 * 1024) / (Mv * 128 * 2);
+  // head-mode kernels run for 100+ us: a smaller activation chunk lets three workgroups share a
+  // compute unit, which is worth more than the extra chunk barriers (measured at M = 8, 56, 64)
+  const int budget = g.V >= 0 ? (Mv > 32 ? 32 : 20) * 1024 : 64 * 1024;
+  int kcb = budget / (Mv * 128 * 2);
   if (kcb < 1) kcb = 1;
   if (kcb > g.kb_per_split) kcb = g.kb_per_split;
   g.kc = kcb * 128;
