@@ -98,6 +98,16 @@ def test_full_size_config_1():
     one_step(shape, w, kv, tok, g, pos, label="config 1 full size")
 
 
+@pytest.mark.timeout(900)
+def test_full_size_config_2_five_rows():
+    """Qwen3-8B-like sizes with more than four rows: the split-K matrix-core projections with their
+    reducing epilogues at full width (steps of up to four rows take the row-streaming path)."""
+    shape = gen.scaled(gen.config(2), B=5, ctx=(2048, 4096))
+    w, kv, tok, g, pos = setup(shape, 0, paged=True, norms=False)
+    w = force_draft_gap(shape, w, kv, tok, g, pos)
+    one_step(shape, w, kv, tok, g, pos, label="config 2 sizes, 5 rows")
+
+
 def test_prepared_workspace_flag_gives_the_same_results_call_after_call():
     """With the workspace zero-filled once and the flag set, the call skips clearing its
     arrival counters; every kernel must leave them at zero for the next call."""
