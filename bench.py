@@ -313,6 +313,8 @@ def main():
                                "round = k draft steps + 1 target-layer verify attention + LM-head argmax + accept/exit",
                    "launch": "hip-graph replay" if graph_ms is not None else "eager"},
         "draft_tokens_verified_per_s": shape.B * (shape.n_q - 1) * 1000.0 / ms,
+        # tokens the planted acceptance pattern yields per round: accepted drafts + the recover token
+        "accepted_tokens_per_s": float(rnd.accept_len.float().sum().item() + shape.B) * 1000.0 / ms,
         "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
         "roofline": {"kernel": "k_gemm_mfma<1,2,true> (widened-head GEMM + argmax of the draft step)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
