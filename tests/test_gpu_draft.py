@@ -123,3 +123,23 @@ def test_prepared_workspace_flag_gives_the_same_results_call_after_call():
         b = prep.step(tok, g, pos + it, flags=prep.lib.FLAG_WORKSPACE_PREPARED)
         for k in a:
             np.testing.assert_array_equal(a[k], b[k], err_msg=f"call {it} {k}")
+
+
+def test_reducing_epilogues_give_identical_bits_every_time():
+    """The split-K sums are finished by whichever workgroup arrives last, always in the same
+    order: forty repetitions of one step (six rows: the matrix-core path) must agree bit for bit,
+    outputs and cache entry alike."""
+    shape = gen.scaled(gen.config(2), D=1024, Hq=8, Hkv=2, d=128, I=2560, V=9000, B=6, ctx=(100, 900), k=2)
+    w, kv, tok, g, pos = setup(shape, 11, paged=True, std=0.05)
+    gd = GpuDraft(shape, w, kv)
+    first, cache0 = None, None
+    for it in range(40):
+        out = gd.step(tok, g, pos)
+        gk, gv = gd.cache()
+        if first is None:
+            first, cache0 = out, (gk, gv)
+            continue
+        for k in out:
+            np.testing.assert_array_equal(out[k], first[k], err_msg=f"repetition {it}: {k}")
+        np.testing.assert_array_equal(gk, cache0[0])
+        np.testing.assert_array_equal(gv, cache0[1])
