@@ -114,7 +114,12 @@ __device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_ld
   const int Mv = g.M * PLANES;
   const int groups = kc >> 3;
   for (int idx = threadIdx.x; idx < g.M * groups; idx += nthreads) {
-    const int m = idx / groups, g8 = idx - m * groups;
+    // four neighbouring lanes take the four 8-wide pieces of one row's 32 k (64 or 128 contiguous
+    // bytes in memory), the next four lanes the next row: the LDS writes of a wave then spread
+    // over all banks instead of marching down one column at the row stride Mv * 16 bytes
+    const int sm = idx >> 2;
+    const int s_ = sm / g.M, m = sm - s_ * g.M;
+    const int g8 = s_ * 4 + (idx & 3);
     const int k = k0 + g8 * 8;
     uint4 hi, lo = make_uint4(0, 0, 0, 0);
     if (g.a_mode == 0 || g.a_mode == 3 || g.a_mode == 4) {
