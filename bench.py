@@ -88,6 +88,7 @@ class Round:
             self.n_draft_steps = shape.k
         case = gen.accept_case(shape, seed, parent=parent if shape.tree else None)
         self.block_tok = dev(case.block_tok)
+        self.planted_len = case.planted_len
         self.split = dev(case.split_tok)
         self.S = len(case.split_tok)
         series, _ = gen.signal_series(shape, seed)
@@ -136,6 +137,28 @@ class Round:
                                 self.sig[0], self.ctx, self.split, self.S, self.ewma, self.n_obs, self.thinking, None,
                                 self.accept_len, self.accept_path, self.recover, self.last_node, self.exit_flag,
                                 self.new_ctx)
+
+
+def plant_acceptance(rnd: Round):
+    """Rewrite the block's draft tokens so that, against the argmaxes the LM head really produces for the
+    block's hidden rows, each sequence accepts the generator's planted number of drafts (a root path of
+    lowest-index children) and the next one differs.  Input preparation, outside every timed region."""
+    torch, s = rnd.torch, rnd.shape
+    am = rnd.target_argmax.cpu().numpy().reshape(s.B, s.n_q)
+    tok = rnd.block_tok.cpu().numpy().copy()
+    par = rnd.parent.cpu().numpy() if rnd.parent is not None else np.tile(np.arange(-1, s.n_q - 1), (s.B, 1))
+    for b in range(s.B):
+        cur = 0
+        for step in range(int(rnd.planted_len[b]) + 1):
+            kids = [c for c in range(1, s.n_q) if par[b, c] == cur]
+            for c in kids:                                   # nobody matches by accident
+                if tok[b, c] == am[b, cur]:
+                    tok[b, c] = (tok[b, c] + 1) % (s.V - 1)
+            if not kids or step == int(rnd.planted_len[b]):
+                break
+            tok[b, kids[0]] = am[b, cur]
+            cur = kids[0]
+    rnd.block_tok.copy_(torch.from_numpy(tok).cuda())
 
 
 def cpu_baseline(rnd: Round):
@@ -205,6 +228,7 @@ def main():
     for _ in range(max(args.warmup, 1)):
         rnd.run()
     torch.cuda.synchronize()
+    plant_acceptance(rnd)
     if args.copy_probe:
         src = rnd.wt["w_head"]
         dst = torch.empty_like(src)
