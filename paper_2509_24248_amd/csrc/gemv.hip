@@ -3,7 +3,7 @@
 //
 // With so few activation rows the matrix cores buy nothing: the kernel is a pure weight
 // stream.  A wave takes two weight rows at a time and reads each along K with 16-byte loads,
-// 1 KB per instruction and up to eight instructions per row in flight, multiplies with the
+// 1 KB per instruction and three instructions per row in flight (more waves resident beat deeper queues), multiplies with the
 // fp32 activations held in LDS and reduces across its lanes.  There is no split over K, so
 // nothing is left for a later kernel (or a last-arriving workgroup) to add up: the epilogue
 // runs in the wave that owns the rows.  The two rows of a pair are chosen by the epilogue:
@@ -36,7 +36,7 @@ __device__ __forceinline__ const char* weight_row(const GemvArgs& g, int n) {
   return static_cast<const char*>(g.w[s]) + static_cast<size_t>(n - start) * g.K * 2;
 }
 
-constexpr int kStepsInFlight = 8;   // 16-byte loads per row in flight
+constexpr int kStepsInFlight = 3;   // 16-byte loads per row in flight (2 rows): few registers, more resident waves (measured best of 1..8)
 
 // LDS position (in floats) of activation row m, element k: step j = k / 512 holds lane
 // l = (k % 512) / 8's eight values as float4 [j][m][half][l]
