@@ -251,11 +251,12 @@ bool gemv_supported(int M, int N, int K) {
   return M >= 1 && M <= 4 && (K % 512) == 0 && (N % 2) == 0 && gemv_lds_bytes(g) <= 144 * 1024;
 }
 
-// One pair per wave at a time.  Few pairs: small workgroups so that the rows spread over all
-// compute units; many pairs: eight waves share one staging of the activations.
+// One pair per wave at a time, eight waves per workgroup sharing one staging of the activations
+// (smaller workgroups for the narrow projections were measured slower), at most three
+// workgroups per compute unit.
 void gemv_plan(GemvArgs& g, int num_cus) {
   const int P = g.N / 2;
-  g.waves = P >= 16 * num_cus ? 8 : 4;
+  g.waves = 8;
   int grid = (P + g.waves - 1) / g.waves;
   const int cap = 3 * num_cus;
   if (grid > cap) grid = cap;
