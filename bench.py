@@ -340,7 +340,8 @@ def main():
         # tokens the planted acceptance pattern yields per round: accepted drafts + the recover token
         "accepted_tokens_per_s": float(rnd.accept_len.float().sum().item() + shape.B) * 1000.0 / ms,
         "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
-        "roofline": {"kernel": "k_gemm_mfma<1,2,true> (widened-head GEMM + argmax of the draft step)",
+        "roofline": {"kernel": (f"k_gemv<{shape.B},2> with the head epilogue" if shape.B <= 4 and shape.dtype == "bf16" and shape.D % 512 == 0
+                                else "k_gemm_mfma<..,2,true>") + " (widened-head GEMM + argmax of the draft step)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(shape.name),
                      "bytes_per_launch": head_bytes, "avg_launch_ms": head_ms},

@@ -145,7 +145,7 @@ struct DraftPlan {
   int Kmax;
   GemmArgs fc, qkv, o, gu, down, head;
   bool gemv;         // few rows: the layer's projections run as row-streaming GEMVs
-  GemvArgs vfc, vqkv, vo, vgu, vdown;
+  GemvArgs vfc, vqkv, vo, vgu, vdown, vhead;
   AttnArgs attn;
   size_t partial_bytes;
   int ntiles_head;
@@ -229,6 +229,8 @@ int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specex
     p.vgu.seg_end[0] = I;
     p.vgu.seg_end[1] = p.vgu.seg_end[2] = 2 * I;
     plan_v(p.vdown, D, I);
+    plan_v(p.vhead, dm.V + 3, D);
+    gemv_plan(p.vhead, num_cus(), 2);   // the long stream does best with two workgroups per compute unit
   }
   plan_gemm(p.head, dm.V + 3, D, B, 2, p.mfma, dm.V);
   p.head.n_extra = 3;
@@ -502,6 +504,20 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
                                            nullptr, io.hidden_out, b.act, s), "norm final"))) return rc;
   }
   // widened head (Eq. 1): argmax (or the top_b best) over the vocabulary rows, three signal rows on the side
+  if (p.gemv && p.top_b == 1 && !io.cand_logit) {
+    // few rows, argmax only: the head is a row stream like the other projections
+    GemvArgs g = p.vhead;
+    g.w[0] = w->w_head;
+    g.a_mode = 3; g.a_src = p.head.a_src; g.a_ssq = p.head.a_ssq; g.a_nssq = p.head.a_nssq; g.a_gain = w->ln_final;
+    g.a_eps = dm.rms_eps;
+    g.epi = 3; g.V = dm.V; g.n_extra = 3; g.part_val = b.part_val; g.part_idx = b.part_idx; g.extra_out = b.extra;
+    {
+      ProfScope prof(SPECEXIT_PROF_DRAFT_HEAD_GEMM, s);
+      if ((rc = check_hip(launch_gemv(g, s), "gemv head"))) return rc;
+    }
+    return check_hip(launch_argmax_finalize(b.part_val, b.part_idx, g.grid, B, io.cand_tok, nullptr, s, b.extra,
+                                            dm.rem_activation, io.sig_raw, io.sig), "argmax finalize");
+  }
   {
     ProfScope prof(SPECEXIT_PROF_DRAFT_HEAD_GEMM, s);
     if ((rc = run_gemm(p.head, mf, bf16, w->w_head, nullptr, nullptr, b, s, "gemm head"))) return rc;

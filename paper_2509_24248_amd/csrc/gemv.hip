@@ -11,11 +11,16 @@
 //            squares for the RMSNorm the consumer applies while staging;
 //   rotary   (head*d + c, head*d + c + d/2) of the concatenated q|k|v projection: the pair
 //            is rotated and stored as a query element or a cache entry (Sec. 3.1 draft layer);
-//   gate     (p, I + p) of the concatenated gate|up projection: silu(gate) * up.
+//   gate     (p, I + p) of the concatenated gate|up projection: silu(gate) * up;
+//   head     (2p, 2p+1) of the widened head (Eq. 1): rows below V enter a running argmax (lowest
+//            index on ties) kept per wave and merged per workgroup, the signal rows V.. are
+//            written out; a later launch merges the workgroups' candidates.
 // Activations are staged once per workgroup as fp32, interleaved so that lane l's eight
 // values of step j are two conflict-free float4 reads.
 #include "common.hpp"
 #include "kernels.hpp"
+
+#include <limits.h>
 
 namespace sx {
 
@@ -36,6 +41,7 @@ __device__ __forceinline__ const char* weight_row(const GemvArgs& g, int n) {
   return static_cast<const char*>(g.w[s]) + static_cast<size_t>(n - start) * g.K * 2;
 }
 
+constexpr int kHeadStepsInFlight = 2;
 constexpr int kStepsInFlight = 3;   // 16-byte loads per row in flight (2 rows): few registers, more resident waves (measured best of 1..8)
 
 // LDS position (in floats) of activation row m, element k: step j = k / 512 holds lane
@@ -45,7 +51,7 @@ __device__ __forceinline__ int act_pos(int M, int m, int k) {
   return (((j * M + m) * 2 + (e >> 2)) * 64 + l) * 4 + (e & 3);
 }
 
-template <int MR>
+template <int MR, int SIF>
 __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
   extern __shared__ float lds[];
   __shared__ float rs_sh[4];
@@ -96,12 +102,14 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
   __syncthreads();
 
   // ---- the workgroup's pairs of rows, one pair per wave at a time
-  const int P = g.N >> 1;
+  const int P = (g.N + 1) >> 1;          // only the head's row count can be odd: its last pair is half empty
   const int ppw = (P + gridDim.x - 1) / gridDim.x;
   const int p_begin = blockIdx.x * ppw, p_end = min(P, p_begin + ppw);
   float ssq[MR];
+  float bestv[MR];
+  int besti[MR];
 #pragma unroll
-  for (int m = 0; m < MR; ++m) ssq[m] = 0.f;
+  for (int m = 0; m < MR; ++m) { ssq[m] = 0.f; bestv[m] = -INFINITY; besti[m] = INT_MAX; }
 
   for (int p = p_begin + wv; p < p_end; p += nwaves) {
     int n1, n2;
@@ -118,21 +126,21 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
       n2 = n1 + 1;
     }
     const char* r1 = weight_row(g, n1) + lane * 16;
-    const char* r2 = weight_row(g, n2) + lane * 16;
+    const char* r2 = weight_row(g, min(n2, g.N - 1)) + lane * 16;   // a row past the end repeats the last one, unused
     float acc1[MR], acc2[MR];
 #pragma unroll
     for (int m = 0; m < MR; ++m) { acc1[m] = 0.f; acc2[m] = 0.f; }
-    for (int j0 = 0; j0 < steps; j0 += kStepsInFlight) {
-      uint4 w1[kStepsInFlight], w2[kStepsInFlight];
+    for (int j0 = 0; j0 < steps; j0 += SIF) {
+      uint4 w1[SIF], w2[SIF];
 #pragma unroll
-      for (int u = 0; u < kStepsInFlight; ++u) {
+      for (int u = 0; u < SIF; ++u) {
         const int j = j0 + u;
         const bool ok = j < steps;
         w1[u] = ok ? load_stream16(r1 + (static_cast<size_t>(j) << 10)) : make_uint4(0, 0, 0, 0);
         w2[u] = ok ? load_stream16(r2 + (static_cast<size_t>(j) << 10)) : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
-      for (int u = 0; u < kStepsInFlight; ++u) {
+      for (int u = 0; u < SIF; ++u) {
         const int j = j0 + u;
         if (j < steps) {
           float f1[8], f2[8];
@@ -170,6 +178,14 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
         ssq[m] += x1 * x1 + x2 * x2;
       } else if (g.epi == 2) {
         g.out_x[static_cast<size_t>(m) * P + p] = v1 * sigmoidf_(v1) * v2;
+      } else if (g.epi == 3) {
+        // rows are visited in increasing order by this wave, '>' keeps the lowest index
+        if (n1 < g.V) { if (v1 > bestv[m]) { bestv[m] = v1; besti[m] = n1; } }
+        else if (g.extra_out) g.extra_out[m * g.n_extra + (n1 - g.V)] = v1;
+        if (n2 < g.N) {
+          if (n2 < g.V) { if (v2 > bestv[m]) { bestv[m] = v2; besti[m] = n2; } }
+          else if (g.extra_out) g.extra_out[m * g.n_extra + (n2 - g.V)] = v2;
+        }
       } else {
         const RopeArgs& ra = g.rope;
         const int half = ra.d >> 1;
@@ -209,6 +225,24 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
     }
   }
 
+  // ---- head: the workgroup's best (value, index) per activation row
+  if (g.epi == 3) {
+    __shared__ float bv_sh[8][4];
+    __shared__ int bi_sh[8][4];
+    if (lane == 0) {
+#pragma unroll
+      for (int m = 0; m < MR; ++m) { bv_sh[wv][m] = bestv[m]; bi_sh[wv][m] = besti[m]; }
+    }
+    __syncthreads();
+    if (threadIdx.x < MR) {
+      float bv = bv_sh[0][threadIdx.x];
+      int bi = bi_sh[0][threadIdx.x];
+      for (int w = 1; w < nwaves; ++w)
+        if (better(bv_sh[w][threadIdx.x], bi_sh[w][threadIdx.x], bv, bi)) { bv = bv_sh[w][threadIdx.x]; bi = bi_sh[w][threadIdx.x]; }
+      g.part_val[threadIdx.x * gridDim.x + blockIdx.x] = bv;
+      g.part_idx[threadIdx.x * gridDim.x + blockIdx.x] = bi;
+    }
+  }
   // ---- this workgroup's piece of the rows' sums of squares (waves added in a fixed order)
   if (g.epi == 0 && g.out_ssq) {
     if (lane == 0) {
@@ -224,18 +258,25 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
   }
 }
 
-template <int MR>
-hipError_t launch_mr(const GemvArgs& g, hipStream_t s) {
+template <int MR, int SIF>
+hipError_t launch_mr_sif(const GemvArgs& g, hipStream_t s) {
   const size_t lds = gemv_lds_bytes(g);
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemv<MR>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemv<MR, SIF>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_gemv<MR>), dim3(g.grid), dim3(64 * g.waves), lds, s, g);
+  hipLaunchKernelGGL((k_gemv<MR, SIF>), dim3(g.grid), dim3(64 * g.waves), lds, s, g);
   return hipGetLastError();
+}
+
+// Loads per row in flight: three for the short projections, two for the head's long stream
+// (measured: 1, 3, 4, 5 slower, as are grids of 1, 3, 4, .. workgroups per compute unit).
+template <int MR>
+hipError_t launch_mr(const GemvArgs& g, hipStream_t s) {
+  return g.epi == 3 ? launch_mr_sif<MR, kHeadStepsInFlight>(g, s) : launch_mr_sif<MR, kStepsInFlight>(g, s);
 }
 
 }  // namespace
@@ -248,17 +289,17 @@ bool gemv_supported(int M, int N, int K) {
   GemvArgs g;
   g.M = M;
   g.K = K;
-  return M >= 1 && M <= 4 && (K % 512) == 0 && (N % 2) == 0 && gemv_lds_bytes(g) <= 144 * 1024;
+  return M >= 1 && M <= 4 && (K % 512) == 0 && N >= 2 && gemv_lds_bytes(g) <= 144 * 1024;
 }
 
 // One pair per wave at a time, eight waves per workgroup sharing one staging of the activations
 // (smaller workgroups for the narrow projections were measured slower), at most three
 // workgroups per compute unit.
-void gemv_plan(GemvArgs& g, int num_cus) {
-  const int P = g.N / 2;
+void gemv_plan(GemvArgs& g, int num_cus, int per_cu) {
+  const int P = (g.N + 1) / 2;
   g.waves = 8;
   int grid = (P + g.waves - 1) / g.waves;
-  const int cap = 3 * num_cus;
+  const int cap = per_cu * num_cus;
   if (grid > cap) grid = cap;
   if (grid < 1) grid = 1;
   g.grid = grid;

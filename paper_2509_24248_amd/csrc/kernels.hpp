@@ -92,16 +92,22 @@ struct GemvArgs {
   int epi;               // 0: rows (2p, 2p+1) -> residual add, out_x / out_store / out_ssq
                          // 1: rotary pairs of the q|k|v projection -> q_out / cache entries
                          // 2: (gate p, up p) of the gate|up projection -> out_x[m][p] = silu(gate) * up
+                         // 3: widened head: rows < V -> per-workgroup argmax candidates part_val / part_idx
+                         //    [M][grid], rows V.. -> extra_out [M][n_extra]; N may be odd
   const float* residual;
   float* out_x;
   void* out_store;
   float* out_ssq;        // [M][grid]
+  int V, n_extra;        // epi 3
+  float* part_val;
+  int* part_idx;
+  float* extra_out;
   RopeArgs rope;
   int grid, waves;       // launch shape, from gemv_plan
 };
 bool gemv_supported(int M, int N, int K);
 size_t gemv_lds_bytes(const GemvArgs& g);
-void gemv_plan(GemvArgs& g, int num_cus);
+void gemv_plan(GemvArgs& g, int num_cus, int per_cu = 3);   // at most per_cu workgroups per compute unit
 hipError_t launch_gemv(const GemvArgs& g, hipStream_t s);
 
 inline int gemm_ntiles(int N) { return (N + 15) / 16; }
