@@ -10,3 +10,6 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    if not config.pluginmanager.hasplugin("timeout"):
+        # the per-test limit is pytest-timeout's; without the plugin the mark is only a label
+        config.addinivalue_line("markers", "timeout(seconds): per-test time limit")
