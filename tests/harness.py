@@ -142,7 +142,8 @@ class GpuDraft:
 
     def tree(self, tok0, g0, ctx_len, parent, rank, top_b):
         """Draft a whole tree level by level through specexit_draft_tree_level / specexit_tree_gather.
-        Only index arrays are prepared here; every value comes out of the library."""
+        Only index arrays are prepared here; every value comes out of the library.  tok0, g0 and
+        ctx_len may be device tensors (outputs of earlier calls), which are then used as they are."""
         lib, shape, B = self.lib, self.shape, self.shape.B
         n = len(parent)
         depth = O.tree_depths(parent)
@@ -153,13 +154,14 @@ class GpuDraft:
         Wmax = max(sum(1 for c in range(n) if depth[c] == l and expanded[c]) for l in range(int(depth.max()) + 1))
         ws = workspace(lib.specexit_draft_tree_level_workspace_bytes(self.desc, self.view, B, Wmax, top_b))
         assert ws.numel() > 256, lib.last_error()
-        ctx = i32(ctx_len)
+        as_i32 = lambda a: a if torch.is_tensor(a) else i32(a)
+        ctx, tok0 = as_i32(ctx_len), as_i32(tok0)
         block_tok = torch.zeros((B, n), dtype=torch.int32, device="cuda")
-        block_tok[:, 0] = i32(tok0)
-        tok = i32(tok0).reshape(B, 1).contiguous()
-        hid = dev(g0, shape).reshape(B, 1, shape.D).contiguous()
+        block_tok[:, 0] = tok0
+        tok = tok0.reshape(B, 1).contiguous()
+        hid = (g0 if torch.is_tensor(g0) else dev(g0, shape)).reshape(B, 1, shape.D).contiguous()
         rows = [0]
-        res = {"hidden_out": {}, "cand_tok": {}, "cand_logit": {}, "sig_raw": {}, "sig": {}}
+        res = {"hidden_out": {}, "cand_tok": {}, "cand_logit": {}, "sig_raw": {}, "sig": {}, "sig_dev": {}}
         for level in range(int(depth.max())):
             W = len(rows)
             hout = torch.empty((B, W, shape.D), dtype=tdtype(shape), device="cuda")
@@ -174,6 +176,7 @@ class GpuDraft:
             for j, c in enumerate(rows):
                 res["hidden_out"][c], res["cand_tok"][c], res["cand_logit"][c] = host(hout[:, j]), host(ct[:, j]), host(cl[:, j])
                 res["sig_raw"][c], res["sig"][c] = host(sr[:, j]), host(sg[:, j])
+                res["sig_dev"][c] = sg[:, j].contiguous()
             kids = [c for c in range(n) if depth[c] == level + 1]
             src = [rows.index(int(parent[c])) for c in kids]
             all_tok = torch.empty((B, len(kids)), dtype=torch.int32, device="cuda")
@@ -189,7 +192,7 @@ class GpuDraft:
                                      i32(nxt), ct, hout, tok, hid, None)
             rows = nxt
         torch.cuda.synchronize()
-        res["block_tok"] = host(block_tok)
+        res["block_tok"], res["block_tok_dev"] = host(block_tok), block_tok
         return res
 
 
