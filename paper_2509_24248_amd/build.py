@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libspecexit.so")
 SOURCES = ["api.hip", "gemm.hip", "gemv.hip", "attn.hip", "attn_mfma.hip", "draft.hip", "accept_exit.hip", "kv_compact.hip", "tree.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-FLAGS = (["-Rpass-analysis=kernel-resource-usage"] if os.environ.get("SPECEXIT_RESOURCE_REMARKS") else []) + ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = (["-Rpass-analysis=kernel-resource-usage"] if os.environ.get("SPECEXIT_RESOURCE_REMARKS") else []) + ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          # packed fp32 VALU forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

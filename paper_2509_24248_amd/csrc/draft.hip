@@ -9,16 +9,6 @@ namespace sx {
 
 namespace {
 
-
-__device__ __forceinline__ float block_sum_256(float v, float* sh) {
-  v = wave_sum(v);
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-  __syncthreads();
-  const float r = sh[0] + sh[1] + sh[2] + sh[3];
-  __syncthreads();
-  return r;
-}
-
 // sum over split-K ranges and planes of 8 consecutive outputs of row b
 __device__ __forceinline__ void gather_partial(const float* partial, int nslices, int planes, int B,
                                                int N, int b, int n, float (&f)[8]) {

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void k_gemv_valu(const GemmArgs g) {
 
 // ------------------------------------------------------------------------- MFMA path
 constexpr int kGemmWaves = 8;   // waves per workgroup, one 16-row weight tile each
-constexpr int kHeadWaves = 8;    // head-mode kernels (4 and 16 waves per workgroup were measured slower)
+constexpr int kHeadWaves = 8;    // head-mode kernels (4 and 16 waves per workgroup were measured slower, at 7 and at 56 rows)
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -104,19 +104,19 @@ __device__ __forceinline__ uint4 load_stream16(const char* p) {
 }
 
 // Stage the activations of K elements [k0, k0 + kc) in LDS as MFMA operand pieces:
-// entry ((s * 4 + q) * Mv + v) holds virtual row v's 8 values k0 + 32 s + 8 q .. + 7 as
-// bf16.  Virtual row v = m * PLANES + plane: plane 0 is the bf16 rounding of the value,
+// entry ((s * 4 + q) * S + (v ^ gemm_lds_swizzle(q))), S = gemm_lds_row_stride(Mv), holds virtual row v's 8 values
+// k0 + 32 s + 8 q .. + 7 as bf16.  Virtual row v = m * PLANES + plane: plane 0 is the bf16 rounding of the value,
 // plane 1 the bf16 rounding of what that lost (fp32 activations keep ~16 mantissa bits).
 // rs_lds (mode 3): the rows' 1 / rms, computed once per workgroup.
 template <int PLANES>
 __device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_lds, const float* rs_lds, int k0, int kc,
                                                   int nthreads) {
-  const int Mv = g.M * PLANES;
+  const int Mvs = gemm_lds_row_stride(g.M * PLANES);
   const int groups = kc >> 3;
   for (int idx = threadIdx.x; idx < g.M * groups; idx += nthreads) {
     // four neighbouring lanes take the four 8-wide pieces of one row's 32 k (64 or 128 contiguous
     // bytes in memory), the next four lanes the next row: the LDS writes of a wave then spread
-    // over all banks instead of marching down one column at the row stride Mv * 16 bytes
+    // over the banks instead of marching down one column at the row stride
     const int sm = idx >> 2;
     const int s_ = sm / g.M, m = sm - s_ * g.M;
     const int g8 = s_ * 4 + (idx & 3);
@@ -172,22 +172,24 @@ __device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_ld
                                    : static_cast<const bf16_t*>(g.a_src) + static_cast<size_t>(m) * half + (k - half);
       hi = *reinterpret_cast<const uint4*>(src);
     }
-    const int s = g8 >> 2, q = g8 & 3;
-    a_lds[(s * 4 + q) * Mv + m * PLANES] = hi;
-    if (PLANES == 2) a_lds[(s * 4 + q) * Mv + m * PLANES + 1] = lo;
+    const int sw = gemm_lds_swizzle(g.M * PLANES, PLANES, g8 & 3);
+    a_lds[g8 * Mvs + ((m * PLANES) ^ sw)] = hi;
+    if (PLANES == 2) a_lds[g8 * Mvs + ((m * PLANES + 1) ^ sw)] = lo;
   }
 }
 
 template <int MT, int PLANES, bool HEAD>
-__global__ __launch_bounds__(64 * (HEAD ? kHeadWaves : kGemmWaves)) void k_gemm_mfma(const GemmArgs g) {
+__global__ __launch_bounds__(64 * (HEAD ? kHeadWaves : kGemmWaves))
+void k_gemm_mfma(const GemmArgs g) {
   constexpr int NW = HEAD ? kHeadWaves : kGemmWaves;
   // LDS: [activation pieces of one K chunk][per wave: one 16-row x 128-k weight tile, 4 KB]
   // weight tile entry [row][pos] holds the 16-byte piece (pos ^ row) of that row, so both the
   // coalesced writes and the per-row operand reads touch 16 distinct 16-byte slots
   extern __shared__ uint4 dyn_lds[];
   const int Mv = g.M * PLANES;
+  const int Mvs = gemm_lds_row_stride(Mv);
   uint4* a_lds = dyn_lds;
-  uint4* w_lds = dyn_lds + (g.kc >> 3) * Mv;
+  uint4* w_lds = dyn_lds + (g.kc >> 3) * Mvs;
   float* rs_lds = reinterpret_cast<float*>(w_lds + NW * 256);   // [M] 1 / rms of the rows (a_mode 3)
   if (g.a_mode == 3) {
     // one wave per row: lanes take the pieces in turn, then a fixed-order butterfly
@@ -221,62 +223,134 @@ __global__ __launch_bounds__(64 * (HEAD ? kHeadWaves : kGemmWaves)) void k_gemm_
     src[i] = sg.base + static_cast<size_t>(lr) * row_bytes + static_cast<size_t>((pos ^ r) << 4);
   }
   const int fr = lane & 15, fq = lane >> 4;
+  const int swr = gemm_lds_swizzle(Mv, PLANES, fq);
   uint4* my = w_lds + wv * 256;
 
   f32x4_t acc[MT];
 #pragma unroll
   for (int t = 0; t < MT; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
-  // Split projections run for a few microseconds only: the first block's weights are requested
-  // before the activations are staged, and each further block before the current one is used.
-  constexpr bool PF = !HEAD;
-  uint4 nxt[4];
-  if (PF && active && kb0 < kb1) {
+  // Weight blocks are requested ahead of their use into two register sets used in turn: blocks
+  // kb0, kb0 + 2, .. in A, the others in B.  A set is asked for its next block as soon as its
+  // tile has been written to LDS, so two blocks are in flight during the arithmetic.  The loop
+  // below is written without any branch around those requests (a block index past the end asks
+  // for one fixed 16-byte piece instead, and an odd block count ends with a half step whose
+  // activation operands are forced to zero): a request under a branch makes the compiler merge register
+  // sets after it, and the waits of those copies pull the loads back into the step that issued
+  // them.  Waves of the last workgroup that have no tile of their own redo the last tile for the
+  // same reason and drop the result.
+  // Split projections run for a few microseconds only: their first blocks are requested before
+  // the activations are staged.  A head with more than 32 activation rows has at most two
+  // workgroups per compute unit, each held up by a barrier per block: requests that stay in
+  // flight across those keep the memory system busy.  Heads with few rows have the waves to do
+  // that without and load each block where it is used.
+  constexpr bool AHEAD = !HEAD || MT >= 3;
+  const int kb_last = kb1 - 1;
+  uint4 wA[4], wB[4];
+  const char* const spare = static_cast<const char*>(g.w[0]);   // where requests past the end are pointed
+  auto request = [&](uint4 (&dst)[4], int kb) {
+    const bool real = kb <= kb_last;
+    const size_t off = static_cast<size_t>(real ? kb : 0) << 8;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) nxt[i] = load_stream16(src[i] + (static_cast<size_t>(kb0) << 8));
+    for (int i = 0; i < 4; ++i) dst[i] = load_stream16(real ? src[i] + off : spare);
+  };
+  if constexpr (AHEAD) {
+    request(wA, kb0);
+    request(wB, kb0 + 1);
   }
-  const int kcb = g.kc >> 7;           // 128-element blocks per staged chunk
-  for (int c0 = kb0; c0 < kb1; c0 += kcb) {
-    const int c1 = min(kb1, c0 + kcb);
-    if (c0 != kb0) __syncthreads();    // everyone is done with the previous chunk
-    stage_activations<PLANES>(g, a_lds, rs_lds, c0 << 7, (c1 - c0) << 7, 64 * NW);
+  // one 128-k block: this wave's weight tile (in wr) through its private LDS tile, transposed
+  // into MFMA operands, against the activation pieces at ab0 (k piece 0, row 0 of the block);
+  // dead: the half step past an odd block count
+  auto one_tile = [&](uint4 (&wr)[4], int kb, const uint4* ab0, bool dead) {
+    if constexpr (!AHEAD) request(wr, kb);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) my[(4 * i + (lane >> 4)) * 16 + pos] = wr[i];
+    if constexpr (AHEAD) request(wr, kb + 2);
+    // the tile is private to this wave, whose LDS operations retire in order: a compiler
+    // fence is all that separates the writes from the transposed reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const uint4* ab = ab0 + fq * Mvs;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint4 wf = my[fr * 16 + ((4 * s + fq) ^ fr)];
+      const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, wf);
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        const int v = 16 * t + fr;
+        uint4 af = ab[s * 4 * Mvs + ((v < Mvs ? v : 0) ^ swr)];   // rows Mv.. of the padding: any content, dropped
+        if (v >= Mv || dead) af = make_uint4(0, 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8_t, af), acc[t], 0, 0, 0);
+      }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+  };
+
+  constexpr bool DOUBLE = HEAD && MT >= 5 && PLANES == 1;   // the LM head over more than 64 bf16 rows (a_mode 1)
+  if constexpr (DOUBLE) {
+    // bf16 activations, two LDS buffers of one 128-k block each.  The next block's pieces are
+    // requested before this block's weights and written to the other buffer after the
+    // arithmetic: one barrier per block, no wait for the staging round trip, and the weight
+    // requests stay in flight across the barrier (loads return in order, so a wave that has
+    // its weights also has the pieces it asked for before them).
+    constexpr int NI = (MT + 1) / 2;                   // 16-byte pieces per thread and block
+    const bf16_t* asrc = static_cast<const bf16_t*>(g.a_src);
+    const int npieces = g.M * 16;
+    const int bufsz = 16 * Mvs;
+    size_t st_src[NI];
+    int st_ent[NI];
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+      const int idx = threadIdx.x + j * (64 * NW);
+      const int ii = idx < npieces ? idx : 0;          // past the end: a valid address, nothing written
+      const int sm = ii >> 2;
+      const int s_ = sm / g.M, m = sm - s_ * g.M;
+      const int g8 = s_ * 4 + (ii & 3);
+      st_src[j] = static_cast<size_t>(m) * g.K + g8 * 8;
+      st_ent[j] = idx < npieces ? g8 * Mvs + (m ^ gemm_lds_swizzle(Mv, 1, g8 & 3)) : -1;
+    }
+    u32x4_t st[NI];
+    u32x4_t* a_vec = reinterpret_cast<u32x4_t*>(a_lds);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) st[j] = *reinterpret_cast<const u32x4_t*>(asrc + st_src[j] + (static_cast<size_t>(min(kb0, kb_last)) << 7));
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+      if (st_ent[j] >= 0) a_vec[st_ent[j]] = st[j];
     __syncthreads();
-    if (!active) continue;
-    for (int kb = c0; kb < c1; ++kb) {
-      uint4 wr[4];
-      if (PF) {
+    auto half = [&](uint4 (&wr)[4], int kb, int cur) {
+      const bool dead = kb >= kb1;                     // uniform: every wave skips the same barrier
+      const size_t koff = static_cast<size_t>(min(kb + 1, kb_last)) << 7;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) wr[i] = nxt[i];
-        if (kb + 1 < kb1) {
+      for (int j = 0; j < NI; ++j) st[j] = *reinterpret_cast<const u32x4_t*>(asrc + st_src[j] + koff);
+      one_tile(wr, kb, a_lds + cur * bufsz, dead);
+      if (!dead) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) nxt[i] = load_stream16(src[i] + (static_cast<size_t>(kb + 1) << 8));
-        }
-      } else {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) wr[i] = load_stream16(src[i] + (static_cast<size_t>(kb) << 8));
+        for (int j = 0; j < NI; ++j)
+          if (st_ent[j] >= 0) a_vec[(cur ^ 1) * bufsz + st_ent[j]] = st[j];
+        __syncthreads();
       }
-#pragma unroll
-      for (int i = 0; i < 4; ++i) my[(4 * i + (lane >> 4)) * 16 + pos] = wr[i];
-      // the tile is private to this wave, whose LDS operations retire in order: a compiler
-      // fence is all that separates the writes from the transposed reads
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      const uint4* ab = a_lds + ((kb - c0) * 16 + fq) * Mv;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint4 wf = my[fr * 16 + ((4 * s + fq) ^ fr)];
-        const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, wf);
-#pragma unroll
-        for (int t = 0; t < MT; ++t) {
-          const int v = 16 * t + fr;
-          uint4 af = ab[s * 4 * Mv + (v < Mv ? v : 0)];
-          if (v >= Mv) af = make_uint4(0, 0, 0, 0);
-          acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8_t, af), acc[t], 0, 0, 0);
-        }
+    };
+    for (int kb = kb0; kb < kb1; kb += 2) {
+      half(wA, kb, 0);
+      half(wB, kb + 1, 1);
+    }
+  } else {
+    const int kcb = g.kc >> 7;           // 128-element blocks per staged chunk
+    auto half = [&](uint4 (&wr)[4], int kb) {
+      const bool dead = kb >= kb1;
+      const int in_chunk = (kb - kb0) % kcb;
+      if (in_chunk == 0 && !dead) {
+        if (kb != kb0) __syncthreads();  // everyone is done with the previous chunk
+        stage_activations<PLANES>(g, a_lds, rs_lds, kb << 7, (min(kb1, kb + kcb) - kb) << 7, 64 * NW);
+        __syncthreads();
       }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
+      one_tile(wr, kb, a_lds + in_chunk * 16 * Mvs, dead);
+    };
+    for (int kb = kb0; kb < kb1; kb += 2) {
+      half(wA, kb);
+      half(wB, kb + 1);
     }
   }
   if (!active && (HEAD || g.epi == 0)) return;
@@ -600,7 +674,7 @@ __global__ __launch_bounds__(256) void k_argmax_rows(const float* __restrict__ l
     if (logits_dbg) logits_dbg[static_cast<size_t>(m) * V + n] = v;
     if (better(v, n, bv, bi)) { bv = v; bi = n; }
   }
-  if (extra_out && threadIdx.x < n_extra) extra_out[m * n_extra + threadIdx.x] = row[V + threadIdx.x];
+  if (extra_out && static_cast<int>(threadIdx.x) < n_extra) extra_out[m * n_extra + threadIdx.x] = row[V + threadIdx.x];
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
     const float ov = __shfl_xor(bv, o, 64);
@@ -655,13 +729,19 @@ void choose_ksplit(GemmArgs& g, bool mfma) {
   }
   // activations staged in LDS per chunk: the whole K range if it fits the budget
   const int Mv = g.M * g.planes;
+  const int Mvs = gemm_lds_row_stride(Mv);
   // head-mode kernels run for 100+ us: a smaller activation chunk lets three workgroups share a
   // compute unit, which is worth more than the extra chunk barriers (measured at M = 8, 56, 64)
   const int budget = g.V >= 0 ? (Mv > 32 ? 32 : 20) * 1024 : 64 * 1024;
-  int kcb = budget / (Mv * 128 * 2);
+  int kcb = budget / (Mvs * 128 * 2);
   if (kcb < 1) kcb = 1;
   if (kcb > g.kb_per_split) kcb = g.kb_per_split;
   g.kc = kcb * 128;
+  // a head with more than 64 rows of bf16 activations in one plane (the LM head over a large
+  // block) keeps two LDS buffers of one 128-k block each and refills them behind the
+  // arithmetic: kc = the 256 k the two buffers hold
+  g.a_double = g.V >= 0 && g.planes == 1 && g.M > 64 ? 1 : 0;
+  if (g.a_double) g.kc = 256;
 }
 
 __global__ void k_zero_i32(int* p, int n) {
@@ -686,7 +766,7 @@ hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
 size_t gemm_mfma_lds_bytes(const GemmArgs& g) {
   // activation pieces, one weight tile per wave, the rows' 1 / rms; the reducing epilogue
   // overlays 512 float4 + 512 float on the front
-  const size_t main = (static_cast<size_t>(g.kc >> 3) * g.M * g.planes + static_cast<size_t>(g.V >= 0 ? kHeadWaves : kGemmWaves) * 256) * 16 +
+  const size_t main = (static_cast<size_t>(g.kc >> 3) * gemm_lds_row_stride(g.M * g.planes) + static_cast<size_t>(g.V >= 0 ? kHeadWaves : kGemmWaves) * 256) * 16 +
                       ((static_cast<size_t>(g.M) * sizeof(float) + 15) & ~static_cast<size_t>(15));
   const size_t overlay = g.epi == 0 ? 0 : static_cast<size_t>(64 * kGemmWaves) * 20 + (g.epi == 2 ? static_cast<size_t>(g.M) * 512 : 0);
   return main > overlay ? main : overlay;
@@ -724,6 +804,7 @@ static hipError_t launch_mfma_planes(const GemmArgs& g, hipStream_t s) {
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
+  if (g.a_double && g.a_mode != 1) return hipErrorInvalidValue;   // that kernel reads bf16 rows only
   if (g.V >= 0) return g.planes == 2 ? launch_mfma_planes<2, true>(g, s) : launch_mfma_planes<1, true>(g, s);
   return g.planes == 2 ? launch_mfma_planes<2, false>(g, s) : launch_mfma_planes<1, false>(g, s);
 }

@@ -36,12 +36,21 @@ def test_tiny_fp32_config():
     run_case(gen.scaled(shape, V=4099, D=520), 11, 2, 2, "fp32 ragged")
 
 
-@pytest.mark.parametrize("M", [1, 7, 16, 17, 56, 64, 144])
+@pytest.mark.parametrize("M", [1, 7, 16, 17, 56, 64, 65, 100, 144])
 def test_bf16_mfma_ragged_vocab(M):
-    # 5003 rows: 312 full 16-row tiles and a 11-row tail that also holds the signal rows
+    # 5003 rows: 312 full 16-row tiles and a 11-row tail that also holds the signal rows;
+    # D = 384 is an odd number of 128-wide k blocks (the kernels take them in pairs)
     shape = gen.scaled(gen.config(1), V=5000, D=384)
     err = run_case(shape, M, 3, M, "mfma")
     assert err < 1e-3          # bf16 inputs are exact; only fp32 summation order differs
+
+
+@pytest.mark.parametrize("M,D", [(33, 128), (72, 128), (144, 512), (96, 1280)])
+def test_bf16_mfma_many_rows_other_depths(M, D):
+    # one block, an even count, and ten blocks: the staged-activation buffers of the many-row kernels
+    shape = gen.scaled(gen.config(1), V=3001, D=D)
+    err = run_case(shape, M, 1, M + D, "mfma many rows")
+    assert err < 1e-3
 
 
 def test_bf16_alu_fallback_when_k_is_not_a_multiple_of_128():
