@@ -95,7 +95,15 @@ def test_full_size_config_1():
     shape = gen.config(1)
     w, kv, tok, g, pos = setup(shape, 0, norms=False)
     w = force_draft_gap(shape, w, kv, tok, g, pos)
-    one_step(shape, w, kv, tok, g, pos, label="config 1 full size")
+    ref, got, gd, _ = one_step(shape, w, kv, tok, g, pos, label="config 1 full size")
+    # the launch configuration bench.py times: workspace zero-filled once, flag set (the head's
+    # last workgroup then merges the candidates itself); same bits, call after call
+    prep = GpuDraft(shape, w, kv)
+    prep.lib.specexit_workspace_prepare(prep.ws)
+    for it in range(6):
+        out = prep.step(tok, g, pos, flags=prep.lib.FLAG_WORKSPACE_PREPARED)
+        for k in out:
+            np.testing.assert_array_equal(out[k], got[k], err_msg=f"prepared call {it}: {k}")
 
 
 @pytest.mark.timeout(900)
@@ -118,9 +126,9 @@ def test_prepared_workspace_flag_gives_the_same_results_call_after_call():
     prep = GpuDraft(shape, w, kv)
     prep.ws.fill_(0x5A)                                   # garbage first: prepare must clear it
     prep.lib.specexit_workspace_prepare(prep.ws)
-    for it in range(4):
-        a = plain.step(tok, g, pos + it)
-        b = prep.step(tok, g, pos + it, flags=prep.lib.FLAG_WORKSPACE_PREPARED)
+    for it in range(12):
+        a = plain.step(tok, g, pos + it % 3)
+        b = prep.step(tok, g, pos + it % 3, flags=prep.lib.FLAG_WORKSPACE_PREPARED)
         for k in a:
             np.testing.assert_array_equal(a[k], b[k], err_msg=f"call {it} {k}")
 
