@@ -96,8 +96,8 @@ def test_full_size_config_1():
     w, kv, tok, g, pos = setup(shape, 0, norms=False)
     w = force_draft_gap(shape, w, kv, tok, g, pos)
     ref, got, gd, _ = one_step(shape, w, kv, tok, g, pos, label="config 1 full size")
-    # the launch configuration bench.py times: workspace zero-filled once, flag set (the head's
-    # last workgroup then merges the candidates itself); same bits, call after call
+    # the launch configuration bench.py times: workspace zero-filled once, flag set; same bits,
+    # call after call
     prep = GpuDraft(shape, w, kv)
     prep.lib.specexit_workspace_prepare(prep.ws)
     for it in range(6):
