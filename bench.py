@@ -305,12 +305,23 @@ def main():
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
     s_ = rnd.shape
+    # the verify-attention call alone re-reads a cache of a few MB .. GB: cycle through copies that
+    # together exceed the 256 MB last-level cache, so that no call is served from it
+    kv_alloc = (rnd.tk.numel() + rnd.tv.numel()) * rnd.tk.element_size()
+    n_copies = 1 if kv_alloc >= (512 << 20) else min(64, -(-(512 << 20) // kv_alloc))
+    kv_keep = [(rnd.tk.clone(), rnd.tv.clone()) for _ in range(n_copies - 1)]
+    kv_views = [rnd.tview] + [sx.kv_view(k_, v_, rnd.tpt) for k_, v_ in kv_keep]
+    turn = [0]
+
+    def attn_call():
+        turn[0] = (turn[0] + 1) % n_copies
+        sx.specexit_verify_attn(kv_views[turn[0]], s_.B, s_.n_q, s_.Hq, rnd.q, rnd.ctx, rnd.mask, rnd.scale,
+                                rnd.attn_out, rnd.ws_attn)
     calls = {
         "specexit_draft_step": per_call(lambda: sx.specexit_draft_step(
             rnd.desc, rnd.w, rnd.dview, s_.B, rnd.tok0, rnd.g0, rnd.pos[0], rnd.hid[0], rnd.next_tok[0], rnd.sig_raw[0],
             rnd.sig[0], rnd.ws_draft, flags=sx.FLAG_WORKSPACE_PREPARED)),
-        "specexit_verify_attn": per_call(lambda: sx.specexit_verify_attn(
-            rnd.tview, s_.B, s_.n_q, s_.Hq, rnd.q, rnd.ctx, rnd.mask, rnd.scale, rnd.attn_out, rnd.ws_attn)),
+        "specexit_verify_attn": per_call(attn_call, n=max(20, n_copies)),
         "specexit_lmhead_argmax": per_call(lambda: sx.specexit_lmhead_argmax(
             rnd.code, s_.B * s_.n_q, s_.D, s_.V, 0, rnd.block_hidden, rnd.lm, rnd.target_argmax, workspace=rnd.ws_head)),
         "specexit_accept_exit": per_call(lambda: sx.specexit_accept_exit(
@@ -349,6 +360,8 @@ def main():
             "lmhead_gemm": {"avg_launch_ms": lm_ms, "achieved_GBs": lm_bytes / (lm_ms * 1e-3) / 1e9, "bytes": lm_bytes},
             "verify_attn_split": {"avg_launch_ms": attn_ms, "achieved_GBs": kv_bytes / (attn_ms * 1e-3) / 1e9, "bytes": kv_bytes}},
         "eager_ms_per_call": calls,
+        "per_call_note": f"back-to-back calls of one export; verify_attn cycles through {n_copies} copies of the KV cache "
+                         f"({n_copies * kv_alloc / 1e6:.0f} MB in all) so that no call is served from the 256 MB last-level cache",
         "projection": {"what": "verify attention call time x target layers (the round above holds one target layer's attention "
                                "and no target MLP / projection GEMMs)", "n_layers": n_layers,
                        "verify_attn_ms_all_layers": calls["specexit_verify_attn"] * n_layers},
