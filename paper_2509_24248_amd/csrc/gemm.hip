@@ -104,9 +104,10 @@ __device__ __forceinline__ uint4 load_stream16(const char* p) {
 }
 
 // Stage the activations of K elements [k0, k0 + kc) in LDS as MFMA operand pieces:
-// entry ((s * 4 + q) * S + (v ^ gemm_lds_swizzle(q))), S = gemm_lds_row_stride(Mv), holds virtual row v's 8 values
-// k0 + 32 s + 8 q .. + 7 as bf16.  Virtual row v = m * PLANES + plane: plane 0 is the bf16 rounding of the value,
-// plane 1 the bf16 rounding of what that lost (fp32 activations keep ~16 mantissa bits).
+// entry ((s * 4 + q) * S + (v ^ gemm_lds_swizzle(q))), S = gemm_lds_row_stride(Mv), holds virtual
+// row v's 8 values k0 + 32 s + 8 q .. + 7 as bf16.  Virtual row v = m * PLANES + plane: plane 0 is
+// the bf16 rounding of the value, plane 1 the bf16 rounding of what that lost (fp32 activations
+// keep ~16 mantissa bits).
 // rs_lds (mode 3): the rows' 1 / rms, computed once per workgroup.
 template <int PLANES>
 __device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_lds, const float* rs_lds, int k0, int kc,
@@ -182,7 +183,7 @@ template <int MT, int PLANES, bool HEAD>
 __global__ __launch_bounds__(64 * (HEAD ? kHeadWaves : kGemmWaves))
 void k_gemm_mfma(const GemmArgs g) {
   constexpr int NW = HEAD ? kHeadWaves : kGemmWaves;
-  // LDS: [activation pieces of one K chunk][per wave: one 16-row x 128-k weight tile, 4 KB]
+  // LDS: [activation pieces of one K chunk, or two one-block buffers][per wave: one 16-row x 128-k weight tile, 4 KB]
   // weight tile entry [row][pos] holds the 16-byte piece (pos ^ row) of that row, so both the
   // coalesced writes and the per-row operand reads touch 16 distinct 16-byte slots
   extern __shared__ uint4 dyn_lds[];
@@ -205,7 +206,7 @@ void k_gemm_mfma(const GemmArgs g) {
   const int wv = threadIdx.x >> 6;
   const int ntiles = (g.N + 15) >> 4;
   const int tile = blockIdx.x * NW + wv;
-  const bool active = tile < ntiles;   // idle waves still take part in the barriers
+  const bool active = tile < ntiles;   // waves past the last tile redo it (same barriers, same requests) and drop the result
   const int ks = blockIdx.y;
   const int KB = g.K >> 7;
   const int kb0 = ks * g.kb_per_split;
@@ -235,13 +236,13 @@ void k_gemm_mfma(const GemmArgs g) {
   // tile has been written to LDS, so two blocks are in flight during the arithmetic.  The loop
   // below is written without any branch around those requests (a block index past the end asks
   // for one fixed 16-byte piece instead, and an odd block count ends with a half step whose
-  // activation operands are forced to zero): a request under a branch makes the compiler merge register
-  // sets after it, and the waits of those copies pull the loads back into the step that issued
-  // them.  Waves of the last workgroup that have no tile of their own redo the last tile for the
+  // activation operands are forced to zero): a request under a branch makes the compiler merge
+  // register sets after it, and the waits of those copies pull the loads back into the step that
+  // issued them.  Waves of the last workgroup that have no tile of their own redo the last tile for the
   // same reason and drop the result.
   // Split projections run for a few microseconds only: their first blocks are requested before
   // the activations are staged.  A head with more than 32 activation rows has at most two
-  // workgroups per compute unit, each held up by a barrier per block: requests that stay in
+  // workgroups per compute unit, each held up by barriers per chunk or block: requests that stay in
   // flight across those keep the memory system busy.  Heads with few rows have the waves to do
   // that without and load each block where it is used.
   constexpr bool AHEAD = !HEAD || MT >= 3;
