@@ -268,29 +268,35 @@ def main():
     # ---- timed region for `value`: K rounds, replayed from a HIP graph unless --no-graph
     graph_ms = None
     if not args.no_graph:
+        graph = None
         try:
             gstream = torch.cuda.Stream()
             gstream.wait_stream(stream)
             with torch.cuda.stream(gstream):
                 rnd.run()
                 torch.cuda.synchronize()
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph, stream=gstream):
+                sx.specexit_graph_begin(gstream)            # the library's own record / replay calls
+                try:
                     rnd.run()
-            torch.cuda.synchronize()
-            for _ in range(max(args.warmup, 1)):
-                graph.replay()
-            torch.cuda.synchronize()
-            g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            g0.record(stream)
-            for _ in range(K):
-                graph.replay()
-            g1.record(stream)
-            torch.cuda.synchronize()
+                finally:
+                    graph = sx.specexit_graph_end(gstream)
+                torch.cuda.synchronize()
+                for _ in range(max(args.warmup, 1)):
+                    sx.specexit_graph_launch(graph, gstream)
+                torch.cuda.synchronize()
+                g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                g0.record(gstream)
+                for _ in range(K):
+                    sx.specexit_graph_launch(graph, gstream)
+                g1.record(gstream)
+                torch.cuda.synchronize()
             graph_ms = g0.elapsed_time(g1) / K
         except Exception as exc:                                # report eager numbers if capture is refused
             print(f"[bench] HIP graph capture unavailable ({exc}); reporting eager timing", file=sys.stderr)
             graph_ms = None
+        finally:
+            if graph is not None:
+                sx.specexit_graph_destroy(graph)
     ms = graph_ms if graph_ms is not None else eager_ms
 
     # ---- time per call of each export (back-to-back calls of one export, outside the timed region)

@@ -145,6 +145,26 @@ int32_t specexit_draft_step(const specexit_model_desc *desc, const specexit_draf
 size_t specexit_draft_step_workspace_bytes(const specexit_model_desc *desc,
                                            const specexit_kv_view *draft_kv, int32_t B);
 
+/* ---- replaying a fixed sequence of calls (Alg. 1's round: draft steps, verification, head,
+ * acceptance; the abstract's and Sec. 1's point is that exit detection must add no overhead to
+ * the decode loop, and at batch 1 that loop is a chain of some sixty short launches) ----
+ * specexit_graph_begin puts `stream` (not the null stream) into HIP stream capture; every call of
+ * this library enqueued on it until specexit_graph_end is recorded instead of run, with the
+ * pointers, sizes and flags passed then.  specexit_graph_end returns an executable graph that
+ * specexit_graph_launch replays on any stream: all recorded kernels in their order, reading and
+ * writing the same device buffers (which the caller keeps alive and may refill between
+ * replays).  Each entry point must have been called once with the same shapes before the
+ * capture (first calls set kernel attributes and query the device, which capture forbids), and
+ * nothing else may use the stream or allocate device memory on this thread while capturing.
+ * The graph owns no buffers; specexit_graph_destroy releases it.  Host pointers: `out` and the
+ * graph handle.  Errors: SPECEXIT_EINVAL (null arguments), SPECEXIT_ELAUNCH (the runtime
+ * refused; the capture is ended and dropped). */
+typedef struct specexit_graph specexit_graph;
+int32_t specexit_graph_begin(void *stream);
+int32_t specexit_graph_end(void *stream, specexit_graph **out);
+int32_t specexit_graph_launch(const specexit_graph *graph, void *stream);
+int32_t specexit_graph_destroy(specexit_graph *graph);
+
 /* Zero-fills a workspace (a small kernel on `stream`; see SPECEXIT_FLAG_WORKSPACE_PREPARED). */
 int32_t specexit_workspace_prepare(void *workspace, size_t workspace_bytes, void *stream);
 

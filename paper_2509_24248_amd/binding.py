@@ -25,6 +25,7 @@ EXPORTS = [
     "specexit_verify_attn", "specexit_verify_attn_workspace_bytes",
     "specexit_lmhead_argmax", "specexit_lmhead_argmax_workspace_bytes",
     "specexit_draft_tree_level", "specexit_draft_tree_level_workspace_bytes", "specexit_tree_gather",
+    "specexit_graph_begin", "specexit_graph_end", "specexit_graph_launch", "specexit_graph_destroy",
     "specexit_workspace_prepare", "specexit_accept_exit", "specexit_kv_compact", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
@@ -75,6 +76,14 @@ def _load() -> C.CDLL:
     lib = C.CDLL(LIB_PATH)
     vp, i32, u32, sz, f32 = C.c_void_p, C.c_int32, C.c_uint32, C.c_size_t, C.c_float
     lib.specexit_last_error.restype = C.c_char_p
+    lib.specexit_graph_begin.restype = i32
+    lib.specexit_graph_begin.argtypes = [vp]
+    lib.specexit_graph_end.restype = i32
+    lib.specexit_graph_end.argtypes = [vp, C.POINTER(vp)]
+    lib.specexit_graph_launch.restype = i32
+    lib.specexit_graph_launch.argtypes = [vp, vp]
+    lib.specexit_graph_destroy.restype = i32
+    lib.specexit_graph_destroy.argtypes = [vp]
     lib.specexit_version.restype = u32
     lib.specexit_draft_step_workspace_bytes.restype = sz
     lib.specexit_draft_step_workspace_bytes.argtypes = [C.POINTER(ModelDesc), C.POINTER(KVView), i32]
@@ -211,6 +220,27 @@ def specexit_draft_step(desc: ModelDesc, w: DraftWeights, draft_kv: KVView, B: i
     _check(LIB.specexit_draft_step(C.byref(desc), C.byref(w), C.byref(draft_kv), B, _ptr(tok), _ptr(hidden_in),
                                    _ptr(pos), _ptr(hidden_out), _ptr(next_tok), _ptr(sig_raw), _ptr(sig),
                                    wp, wb, flags, _stream(stream)))
+
+
+def specexit_graph_begin(stream) -> None:
+    """stream: a torch.cuda.Stream other than the default one; calls of this module made with
+    stream=that stream (or with it current) are recorded until specexit_graph_end."""
+    _check(LIB.specexit_graph_begin(_stream(stream)))
+
+
+def specexit_graph_end(stream):
+    """Returns the graph handle (an opaque pointer) for specexit_graph_launch / _destroy."""
+    handle = C.c_void_p()
+    _check(LIB.specexit_graph_end(_stream(stream), C.byref(handle)))
+    return handle
+
+
+def specexit_graph_launch(graph, stream=None) -> None:
+    _check(LIB.specexit_graph_launch(graph, _stream(stream)))
+
+
+def specexit_graph_destroy(graph) -> None:
+    _check(LIB.specexit_graph_destroy(graph))
 
 
 def specexit_workspace_prepare(workspace, stream=None) -> None:

@@ -761,6 +761,48 @@ int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_
   return check_hip(launch_accept_exit(a, static_cast<hipStream_t>(stream)), "accept_exit");
 }
 
+struct specexit_graph {
+  hipGraphExec_t exec;
+};
+
+int32_t specexit_graph_begin(void* stream) {
+  if (!stream) return fail(SPECEXIT_EINVAL, "graph_begin: the null stream cannot be captured");
+  return check_hip(hipStreamBeginCapture(static_cast<hipStream_t>(stream), hipStreamCaptureModeThreadLocal), "graph_begin");
+}
+
+int32_t specexit_graph_end(void* stream, specexit_graph** out) {
+  if (!stream || !out) return fail(SPECEXIT_EINVAL, "graph_end: null stream or result pointer");
+  *out = nullptr;
+  hipGraph_t graph = nullptr;
+  int32_t rc = check_hip(hipStreamEndCapture(static_cast<hipStream_t>(stream), &graph), "graph_end");
+  if (rc) return rc;
+  if (!graph) return fail(SPECEXIT_ELAUNCH, "graph_end: the capture produced no graph");
+  hipGraphExec_t exec = nullptr;
+  rc = check_hip(hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0), "graph instantiate");
+  (void)hipGraphDestroy(graph);
+  if (rc) return rc;
+  specexit_graph* g = new (std::nothrow) specexit_graph;
+  if (!g) {
+    (void)hipGraphExecDestroy(exec);
+    return fail(SPECEXIT_ELAUNCH, "graph_end: out of host memory");
+  }
+  g->exec = exec;
+  *out = g;
+  return SPECEXIT_OK;
+}
+
+int32_t specexit_graph_launch(const specexit_graph* graph, void* stream) {
+  if (!graph) return fail(SPECEXIT_EINVAL, "graph_launch: null graph");
+  return check_hip(hipGraphLaunch(graph->exec, static_cast<hipStream_t>(stream)), "graph_launch");
+}
+
+int32_t specexit_graph_destroy(specexit_graph* graph) {
+  if (!graph) return SPECEXIT_OK;
+  const hipError_t e = hipGraphExecDestroy(graph->exec);
+  delete graph;
+  return check_hip(e, "graph_destroy");
+}
+
 int32_t specexit_workspace_prepare(void* workspace, size_t workspace_bytes, void* stream) {
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255)) return fail(SPECEXIT_EWORKSPACE, "workspace_prepare: workspace null or not 256-byte aligned");
   if (workspace_bytes / 4 > 0x7fffffff) return fail(SPECEXIT_EINVAL, "workspace_prepare: workspace too large");
