@@ -61,7 +61,7 @@ class Round:
         L = gen.context_lengths(shape, seed)
         self.L = L
         tkv = gen.kv_cache(shape, L, n_q, seed)                       # target layer cache, block K/V in place
-        dkv = gen.kv_cache(shape, L, k + 1, seed, stream=17)          # the draft layer's own cache
+        dkv = gen.kv_cache(shape, L, n_q if shape.tree else k + 1, seed, stream=17)   # the draft layer's own cache (a tree keeps one entry per node)
         self.tk, self.tv = fdev(tkv.k), fdev(tkv.v)
         self.dk, self.dv = fdev(dkv.k), fdev(dkv.v)
         self.tpt = dev(tkv.page_table) if tkv.paged else None
@@ -78,12 +78,16 @@ class Round:
         tok0 = gen.token_ids(shape, B, seed)
         self.tok0 = dev(tok0)
         if shape.tree:
-            parent = gen.random_tree_parents(shape, seed)
+            # one topology for all sequences, numbered level by level; the drafted tree and the
+            # verified block share it
+            par1, rank1 = gen.level_ordered_tree(shape, seed)
+            parent = np.tile(par1, (B, 1)).astype(np.int32)
             mask = gen.ancestor_masks(parent)
             self.parent = dev(parent)
             self.mask = dev(mask.view(np.int64))
             self.n_draft_steps = shape.k                                # one call per tree level
         else:
+            par1 = rank1 = None
             self.parent, self.mask = None, None
             self.n_draft_steps = shape.k
         case = gen.accept_case(shape, seed, parent=parent if shape.tree else None)
@@ -115,15 +119,78 @@ class Round:
         self.ws_attn = ws(sx.specexit_verify_attn_workspace_bytes(self.tview, B, n_q, shape.Hq))
         self.ws_head = ws(sx.specexit_lmhead_argmax_workspace_bytes(self.code, B * n_q, shape.D, shape.V, 0))
         self.scale = shape.d ** -0.5
+        self.levels = self.plan_tree(par1, rank1) if shape.tree else None
         if keep_host:
             host.update(w=w, lm=lm, tkv=tkv, dkv=dkv, q=q, hid=hid, g0=g0, tok0=tok0, case=case, series=series,
                         parent=parent if shape.tree else None, mask=mask if shape.tree else None)
         self.host = host
 
+    def plan_tree(self, parent, rank):
+        """Index arrays and buffers of tree drafting, level by level: the nodes of a level that have
+        children are the rows of that level's specexit_draft_tree_level call; specexit_tree_gather
+        then fills the block's token row and hands tokens and hidden states to the next level."""
+        torch, sx, s = self.torch, self.sx, self.shape
+        from workloads import gen
+        B, n, D = s.B, s.n_q, s.D
+        dt = torch.bfloat16 if s.dtype == "bf16" else torch.float32
+        depth = np.zeros(n, np.int64)
+        for c in range(1, n):
+            depth[c] = depth[parent[c]] + 1
+        expanded = [any(int(parent[c]) == p for c in range(1, n)) for p in range(n)]
+        masks = gen.ancestor_masks(np.asarray(parent)[None, :])[0]
+        self.top_b = int(rank.max()) + 1
+        i32 = lambda a: torch.from_numpy(np.asarray(a, np.int32)).cuda()
+        self.block_drafted = torch.zeros((B, n), dtype=torch.int32, device="cuda")
+        self.block_drafted[:, 0] = self.tok0
+        levels, rows = [], [0]
+        tok, hid = self.tok0.reshape(B, 1).contiguous(), self.g0.reshape(B, 1, D).contiguous()
+        for level in range(int(depth.max())):
+            W = len(rows)
+            kids = [c for c in range(n) if depth[c] == level + 1]
+            nxt = [c for c in kids if expanded[c]]
+            lv = dict(level=level, W=W, tok=tok, hid=hid, node=i32(rows),
+                      amask=torch.from_numpy(np.ascontiguousarray(masks[rows]).view(np.int64)).cuda(), n_blk=max(rows) + 1,
+                      hout=torch.empty((B, W, D), dtype=dt, device="cuda"),
+                      ct=torch.empty((B, W, self.top_b), dtype=torch.int32, device="cuda"),
+                      sr=torch.empty((B, W, 3), dtype=torch.float32, device="cuda"),
+                      sg=torch.empty((B, W, 3), dtype=torch.float32, device="cuda"),
+                      kids=i32(kids), n_kids=len(kids), kid_src=i32([rows.index(int(parent[c])) for c in kids]),
+                      kid_rank=i32([rank[c] for c in kids]),
+                      kid_tok=torch.empty((B, len(kids)), dtype=torch.int32, device="cuda"),
+                      n_next=len(nxt))
+            # a workspace of its own per level: the prepared-workspace flag wants one shape per workspace
+            lv["ws"] = torch.empty(max(sx.specexit_draft_tree_level_workspace_bytes(self.desc, self.dview, B, W, self.top_b), 256),
+                                   dtype=torch.uint8, device="cuda")
+            sx.specexit_workspace_prepare(lv["ws"])
+            if nxt:
+                lv.update(nxt=i32(nxt), nxt_src=i32([rows.index(int(parent[c])) for c in nxt]), nxt_rank=i32([rank[c] for c in nxt]))
+                tok = torch.empty((B, len(nxt)), dtype=torch.int32, device="cuda")
+                hid = torch.empty((B, len(nxt), D), dtype=dt, device="cuda")
+                lv.update(tok_next=tok, hid_next=hid)
+            levels.append(lv)
+            if not nxt:
+                break
+            rows = nxt
+        return levels
+
+    def draft_tree(self):
+        sx, s = self.sx, self.shape
+        for lv in self.levels:
+            sx.specexit_draft_tree_level(self.desc, self.w, self.dview, s.B, lv["W"], lv["tok"], lv["hid"], self.ctx,
+                                         lv["level"], lv["node"], lv["amask"], lv["n_blk"], self.top_b, lv["hout"],
+                                         lv["ct"], None, lv["sr"], lv["sg"], lv["ws"], flags=sx.FLAG_WORKSPACE_PREPARED)
+            sx.specexit_tree_gather(self.code, s.B, lv["W"], self.top_b, lv["n_kids"], s.D, s.n_q, lv["kid_src"],
+                                    lv["kid_rank"], lv["kids"], lv["ct"], lv["hout"], lv["kid_tok"], None, self.block_drafted)
+            if lv["n_next"]:
+                sx.specexit_tree_gather(self.code, s.B, lv["W"], self.top_b, lv["n_next"], s.D, s.n_q, lv["nxt_src"],
+                                        lv["nxt_rank"], lv["nxt"], lv["ct"], lv["hout"], lv["tok_next"], lv["hid_next"], None)
+
     def run(self):
         sx, s = self.sx, self.shape
         tok, hin = self.tok0, self.g0
-        for j in range(self.n_draft_steps):
+        if self.levels is not None:
+            self.draft_tree()
+        for j in range(0 if self.levels is not None else self.n_draft_steps):
             hout = self.hid[j & 1]
             sx.specexit_draft_step(self.desc, self.w, self.dview, s.B, tok, hin, self.pos[j], hout,
                                    self.next_tok[j], self.sig_raw[j], self.sig[j], self.ws_draft,
@@ -133,8 +200,9 @@ class Round:
                                 self.attn_out, self.ws_attn)
         sx.specexit_lmhead_argmax(self.code, s.B * s.n_q, s.D, s.V, 0, self.block_hidden, self.lm,
                                   self.target_argmax, workspace=self.ws_head)
+        sig0 = self.sig[0] if self.levels is None else self.levels[0]["sg"]      # [B, 3] either way (the root level has one row)
         sx.specexit_accept_exit(self.cfg, s.B, s.n_q, self.block_tok, self.parent, self.target_argmax,
-                                self.sig[0], self.ctx, self.split, self.S, self.ewma, self.n_obs, self.thinking, None,
+                                sig0, self.ctx, self.split, self.S, self.ewma, self.n_obs, self.thinking, None,
                                 self.accept_len, self.accept_path, self.recover, self.last_node, self.exit_flag,
                                 self.new_ctx)
 
@@ -335,6 +403,17 @@ def main():
             rnd.ewma, rnd.n_obs, rnd.thinking, None, rnd.accept_len, rnd.accept_path, rnd.recover, rnd.last_node,
             rnd.exit_flag, rnd.new_ctx)),
     }
+    # after the round: cache compaction along the accepted paths of the last round (one layer here)
+    calls["specexit_kv_compact"] = per_call(lambda: sx.specexit_kv_compact(
+        rnd.tview, 1, 0, s_.B, s_.n_q, rnd.ctx, rnd.accept_path, rnd.accept_len, rnd.last_node, rnd.block_hidden, s_.D,
+        rnd.hid[0]))
+    if rnd.levels is not None:
+        wide = max(rnd.levels, key=lambda lv: lv["W"])
+        calls[f"specexit_draft_tree_level (W={wide['W']}, top_b={rnd.top_b})"] = per_call(lambda: sx.specexit_draft_tree_level(
+            rnd.desc, rnd.w, rnd.dview, s_.B, wide["W"], wide["tok"], wide["hid"], rnd.ctx, wide["level"], wide["node"],
+            wide["amask"], wide["n_blk"], rnd.top_b, wide["hout"], wide["ct"], None, wide["sr"], wide["sg"], wide["ws"],
+            flags=sx.FLAG_WORKSPACE_PREPARED))
+        calls["tree drafting, all levels (draft_tree_level + tree_gather)"] = per_call(rnd.draft_tree)
     n_layers = {"tiny_f32": 4, "qwen3_4b_chain": 36, "qwen3_8b_paged": 36, "tree_8b": 36, "qwen3_32b_paged": 64}[shape.name]
 
     e = 2 if shape.dtype == "bf16" else 4
@@ -349,15 +428,17 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": shape.dtype, "data": "synthetic",
-        "config": {"workload": f"configs[{shape.index}] {shape.name}: B={shape.B} chain k={shape.k} n_q={shape.n_q} "
-                               f"ctx={shape.ctx} D={shape.D} Hq/Hkv/d={shape.Hq}/{shape.Hkv}/{shape.d} V={shape.V} I={shape.I}; "
-                               "round = k draft steps + 1 target-layer verify attention + LM-head argmax + accept/exit",
+        "config": {"workload": f"configs[{shape.index}] {shape.name}: B={shape.B} {'tree depth' if shape.tree else 'chain'} k={shape.k} n_q={shape.n_q} "
+                               f"ctx={shape.ctx} D={shape.D} Hq/Hkv/d={shape.Hq}/{shape.Hkv}/{shape.d} V={shape.V} I={shape.I}; " +
+                               ("round = k tree-drafting levels" if shape.tree else "round = k draft steps") +
+                               " + 1 target-layer verify attention + LM-head argmax + accept/exit",
                    "launch": "hip-graph replay" if graph_ms is not None else "eager"},
         "draft_tokens_verified_per_s": shape.B * (shape.n_q - 1) * 1000.0 / ms,
         # tokens the planted acceptance pattern yields per round: accepted drafts + the recover token
         "accepted_tokens_per_s": float(rnd.accept_len.float().sum().item() + shape.B) * 1000.0 / ms,
         "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
-        "roofline": {"kernel": (f"k_gemv<{shape.B},2> with the head epilogue" if shape.B <= 4 and shape.dtype == "bf16" and shape.D % 512 == 0
+        "roofline": {"kernel": ("k_gemm_mfma<..,2,true> with the ranked-candidates epilogue" if shape.tree else
+                                f"k_gemv<{shape.B},2> with the head epilogue" if shape.B <= 4 and shape.dtype == "bf16" and shape.D % 512 == 0
                                 else "k_gemm_mfma<..,2,true>") + " (widened-head GEMM + argmax of the draft step)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(shape.name),

@@ -526,7 +526,8 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     if (p.top_b == 1 && !io.cand_logit)
       return check_hip(launch_argmax_finalize(b.part_val, b.part_idx, p.ntiles_head, B, io.cand_tok, nullptr, s, b.extra,
                                               dm.rem_activation, io.sig_raw, io.sig), "argmax finalize");
-    const int C = p.ntiles_head * p.top_b;
+    // ranked candidates arrive merged per 128-row workgroup, a plain maximum per 16-row tile
+    const int C = (p.top_b > 1 ? gemm_groups(dm.V + 3) : p.ntiles_head) * p.top_b;
     return check_hip(launch_topb_finalize(b.part_val, b.part_idx, C, C, p.top_b, B, io.cand_tok, io.cand_logit, s,
                                           b.extra, dm.rem_activation, io.sig_raw, io.sig), "top-b finalize");
   }

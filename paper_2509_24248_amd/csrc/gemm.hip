@@ -354,7 +354,8 @@ void k_gemm_mfma(const GemmArgs g) {
       half(wB, kb + 1);
     }
   }
-  if (!active && (HEAD || g.epi == 0)) return;
+  // (a head that reports ranked candidates merges them per workgroup below: its idle waves stay)
+  if (!active && (HEAD ? g.top_b <= 1 : g.epi == 0)) return;
 
   // accumulator layout: lane (c = lane % 16, q = lane / 16) holds rows n0 + 4q + i of
   // activation column 16 t + c
@@ -506,8 +507,14 @@ void k_gemm_mfma(const GemmArgs g) {
     return;
   }
   // head mode: fused argmax (or the top_b best, best first) over rows < V of this tile,
-  // signal rows routed to extra_out
+  // signal rows routed to extra_out.  With ranked candidates (top_b > 1) the waves of the
+  // workgroup first merge their tiles' lists through LDS, so the merging launch sees one list per
+  // 128 weight rows instead of one per 16.
   const int TB = g.top_b > 1 ? g.top_b : 1;
+  const bool merge = TB > 1;
+  float* cv = reinterpret_cast<float*>(dyn_lds);              // [wave][M][TB] values, then indices
+  int* ci = reinterpret_cast<int*>(cv + NW * g.M * TB);
+  if (merge) __syncthreads();                                 // every wave is done with the activation pieces
 #pragma unroll
   for (int t = 0; t < MT; ++t) {
     const int v = 16 * t + fr;
@@ -524,7 +531,7 @@ void k_gemm_mfma(const GemmArgs g) {
     for (int i = 0; i < 4; ++i) {
       const int n = n0 + 4 * fq + i;
       cur[i] = -INFINITY;
-      if (owner && n < g.N) {
+      if (owner && active && n < g.N) {
         if (n < g.V) {
           if (g.logits_dbg) g.logits_dbg[static_cast<size_t>(m) * g.V + n] = val[i];
           cur[i] = val[i];
@@ -546,13 +553,50 @@ void k_gemm_mfma(const GemmArgs g) {
         if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
       }
       if (owner && fq == 0) {
-        g.part_val[(static_cast<size_t>(m) * ntiles + tile) * TB + r] = bv;
-        g.part_idx[(static_cast<size_t>(m) * ntiles + tile) * TB + r] = bi;
+        if (merge) {
+          cv[(wv * g.M + m) * TB + r] = bv;
+          ci[(wv * g.M + m) * TB + r] = bi;
+        } else {
+          g.part_val[(static_cast<size_t>(m) * ntiles + tile) * TB + r] = bv;
+          g.part_idx[(static_cast<size_t>(m) * ntiles + tile) * TB + r] = bi;
+        }
       }
       if (r + 1 < TB) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           if (n0 + 4 * fq + i == bi) cur[i] = -INFINITY;   // taken: out of the next pass
+      }
+    }
+  }
+  if (merge) {
+    __syncthreads();
+    // half a wave per activation row, one lane per candidate of the NW lists (at most 8 x 4):
+    // pass r keeps what comes after pass r-1's pick (value descending, lower index first among
+    // equals; INT_MAX marks an empty slot) and takes the best of it by a butterfly
+    for (int m = 2 * wv + (lane >> 5); m < g.M; m += 2 * NW) {
+      const int slot = lane & 31;
+      const bool have = slot < NW * TB;
+      const int w = have ? slot / TB : 0, q = have ? slot - w * TB : 0;
+      const float cval = have ? cv[(w * g.M + m) * TB + q] : -INFINITY;
+      const int cidx = have ? ci[(w * g.M + m) * TB + q] : INT_MAX;
+      float prev_v = INFINITY;
+      int prev_i = -1;
+      for (int r = 0; r < TB; ++r) {
+        const bool after = cval < prev_v || (cval == prev_v && cidx > prev_i);
+        float bv = (cidx != INT_MAX && after) ? cval : -INFINITY;
+        int bi = (cidx != INT_MAX && after) ? cidx : INT_MAX;
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) {
+          const float ov = __shfl_xor(bv, o, 64);
+          const int oi = __shfl_xor(bi, o, 64);
+          if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        if (slot == 0) {
+          g.part_val[(static_cast<size_t>(m) * gridDim.x + blockIdx.x) * TB + r] = bv;
+          g.part_idx[(static_cast<size_t>(m) * gridDim.x + blockIdx.x) * TB + r] = bi;
+        }
+        prev_v = bv;
+        prev_i = bi;
       }
     }
   }
@@ -574,10 +618,20 @@ __global__ __launch_bounds__(kFinalThreads) void k_argmax_finalize(const float* 
   const int m = blockIdx.x;
   float bv = -INFINITY;
   int bi = INT_MAX;
-  for (int t = threadIdx.x; t < ntiles; t += kFinalThreads) {
-    const float v = part_val[static_cast<size_t>(m) * ntiles + t];
-    const int i = part_idx[static_cast<size_t>(m) * ntiles + t];
-    if (better(v, i, bv, bi)) { bv = v; bi = i; }
+  constexpr int U = 10;   // candidates per thread requested at once (9497 tiles of a 151939-row head: 10)
+  for (int t0 = threadIdx.x; t0 < ntiles; t0 += U * kFinalThreads) {
+    float v[U];
+    int i[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int t = t0 + u * kFinalThreads;
+      const bool ok = t < ntiles;
+      v[u] = ok ? part_val[static_cast<size_t>(m) * ntiles + t] : -INFINITY;
+      i[u] = ok ? part_idx[static_cast<size_t>(m) * ntiles + t] : INT_MAX;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (better(v[u], i[u], bv, bi)) { bv = v[u]; bi = i[u]; }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -587,11 +641,21 @@ __global__ __launch_bounds__(kFinalThreads) void k_argmax_finalize(const float* 
   }
   if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    for (int w = 1; w < kFinalThreads / 64; ++w)
-      if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
-    argmax[m] = bi;
-    if (max_logit) max_logit[m] = bv;
+  if (threadIdx.x < 64) {
+    // the 16 waves' results, one per lane, merged by a butterfly
+    const bool have = threadIdx.x < kFinalThreads / 64;
+    bv = have ? sv[threadIdx.x] : -INFINITY;
+    bi = have ? si[threadIdx.x] : INT_MAX;
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) {
+      const float ov = __shfl_xor(bv, o, 64);
+      const int oi = __shfl_xor(bi, o, 64);
+      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+    }
+    if (threadIdx.x == 0) {
+      argmax[m] = bi;
+      if (max_logit) max_logit[m] = bv;
+    }
   }
   if (sig && threadIdx.x == 64) {
     const float zc = extra[m * 3 + 0], zp = extra[m * 3 + 1], zr = extra[m * 3 + 2];
@@ -621,14 +685,50 @@ __global__ __launch_bounds__(kFinalThreads) void k_topb_finalize(const float* __
   const int* ri = idxs ? idxs + static_cast<size_t>(m) * stride : nullptr;
   float prev_v = INFINITY;
   int prev_i = -1;
+  // candidate lists (9497 tiles x 1, or 1188 workgroups x 4 for a 151939-row head) are read once,
+  // all requests at once, and the passes run from registers; a full logits row is streamed in
+  // every pass.  Kept short on purpose: this kernel runs once on a cold instruction cache.
+  constexpr int U = 10;
+  const bool held = ri != nullptr && C <= U * kFinalThreads;
+  float hv[U];
+  int hi[U];
+  if (held) {
+    // slot groups past the end are skipped as a whole (a uniform branch); inside the last group
+    // the last candidate is read again and marked empty
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      hv[u] = -INFINITY;
+      hi[u] = INT_MAX;
+      if (u * kFinalThreads < C) {
+        const int c = threadIdx.x + u * kFinalThreads;
+        const int cc = min(c, C - 1);
+        const float v = rv[cc];
+        const int i = ri[cc];
+        hv[u] = v;
+        hi[u] = c < C ? i : INT_MAX;
+      }
+    }
+  }
   for (int r = 0; r < top_b; ++r) {
     float bv = -INFINITY;
     int bi = INT_MAX;
-    for (int c = threadIdx.x; c < C; c += kFinalThreads) {
-      const float v = rv[c];
-      const int i = ri ? ri[c] : c;
-      const bool after = v < prev_v || (v == prev_v && i > prev_i);
-      if (i != INT_MAX && after && better(v, i, bv, bi)) { bv = v; bi = i; }
+    if (held) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (u * kFinalThreads < C) {
+          const bool after = (hv[u] < prev_v) | ((hv[u] == prev_v) & (hi[u] > prev_i));
+          const bool take = (hi[u] != INT_MAX) & after & better(hv[u], hi[u], bv, bi);
+          bv = take ? hv[u] : bv;
+          bi = take ? hi[u] : bi;
+        }
+      }
+    } else {
+      for (int c = threadIdx.x; c < C; c += kFinalThreads) {
+        const float v = rv[c];
+        const int i = ri ? ri[c] : c;
+        const bool after = v < prev_v || (v == prev_v && i > prev_i);
+        if (i != INT_MAX && after && better(v, i, bv, bi)) { bv = v; bi = i; }
+      }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
@@ -638,13 +738,22 @@ __global__ __launch_bounds__(kFinalThreads) void k_topb_finalize(const float* __
     }
     if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = bv; si[threadIdx.x >> 6] = bi; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      for (int w = 1; w < kFinalThreads / 64; ++w)
-        if (better(sv[w], si[w], bv, bi)) { bv = sv[w]; bi = si[w]; }
-      cand_tok[m * top_b + r] = bi == INT_MAX ? -1 : bi;
-      if (cand_logit) cand_logit[m * top_b + r] = bv;
-      pick_v = bv;
-      pick_i = bi;
+    if (threadIdx.x < 64) {
+      const bool have = threadIdx.x < kFinalThreads / 64;
+      bv = have ? sv[threadIdx.x] : -INFINITY;
+      bi = have ? si[threadIdx.x] : INT_MAX;
+#pragma unroll
+      for (int o = 8; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+      }
+      if (threadIdx.x == 0) {
+        cand_tok[m * top_b + r] = bi == INT_MAX ? -1 : bi;
+        if (cand_logit) cand_logit[m * top_b + r] = bv;
+        pick_v = bv;
+        pick_i = bi;
+      }
     }
     __syncthreads();
     prev_v = pick_v;
