@@ -202,6 +202,14 @@ void k_gemm_mfma(const GemmArgs g) {
     }
     __syncthreads();
   }
+  if (MT >= 2 && Mvs > Mv) {
+    // rows Mv .. Mvs - 1 of every k piece are padding: zero once, staging never touches them
+    const int pad = Mvs - Mv;
+    for (int idx = threadIdx.x; idx < (g.kc >> 3) * pad; idx += 64 * NW) {
+      const int g8 = idx / pad, v = Mv + idx - g8 * pad;
+      a_lds[g8 * Mvs + (v ^ gemm_lds_swizzle(Mv, PLANES, g8 & 3))] = make_uint4(0, 0, 0, 0);
+    }
+  }
   const int lane = threadIdx.x & 63;
   const int wv = threadIdx.x >> 6;
   const int ntiles = (g.N + 15) >> 4;
@@ -280,8 +288,14 @@ void k_gemm_mfma(const GemmArgs g) {
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
         const int v = 16 * t + fr;
-        uint4 af = ab[s * 4 * Mvs + ((v < Mvs ? v : 0) ^ swr)];   // rows Mv.. of the padding: any content, dropped
-        if (v >= Mv || dead) af = make_uint4(0, 0, 0, 0);
+        uint4 af;
+        if constexpr (MT >= 2) {
+          af = ab[s * 4 * Mvs + (v ^ swr)];                        // padding rows Mv.. hold zeros
+        } else {
+          af = ab[s * 4 * Mvs + ((v < Mvs ? v : 0) ^ swr)];
+          if (v >= Mv) af = make_uint4(0, 0, 0, 0);
+        }
+        if (dead) af = make_uint4(0, 0, 0, 0);
         acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8_t, af), acc[t], 0, 0, 0);
       }
     }
