@@ -448,7 +448,9 @@ def main():
             "verify_attn_split": {"avg_launch_ms": attn_ms, "achieved_GBs": kv_bytes / (attn_ms * 1e-3) / 1e9, "bytes": kv_bytes}},
         "eager_ms_per_call": calls,
         "per_call_note": f"back-to-back calls of one export; verify_attn cycles through {n_copies} copies of the KV cache "
-                         f"({n_copies * kv_alloc / 1e6:.0f} MB in all) so that no call is served from the 256 MB last-level cache",
+                         f"({n_copies * kv_alloc / 1e6:.0f} MB in all)" +
+                         (" so that no call is served from the 256 MB last-level cache" if n_copies * kv_alloc >= (512 << 20)
+                          else ": small enough to stay in the 256 MB last-level cache, a cache-resident figure"),
         "projection": {"what": "verify attention call time x target layers (the round above holds one target layer's attention "
                                "and no target MLP / projection GEMMs)", "n_layers": n_layers,
                        "verify_attn_ms_all_layers": calls["specexit_verify_attn"] * n_layers},
