@@ -231,6 +231,13 @@ int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specex
     plan_v(p.vdown, D, I);
     plan_v(p.vhead, dm.V + 3, D);
     gemv_plan(p.vhead, num_cus(), 2);   // the long stream does best with two workgroups per compute unit
+    // a layer that fits the 256 MB last-level cache is read with ordinary loads, so that part of
+    // it is still there one draft step later; a larger one is streamed past the caches
+    const size_t layer_bytes = 2 * (static_cast<size_t>(D) * 2 * D + static_cast<size_t>((dm.Hq + 2 * dm.Hkv) * dm.d) * D +
+                                    static_cast<size_t>(D) * Hd + static_cast<size_t>(3) * I * D);
+    const int stream = layer_bytes > (static_cast<size_t>(240) << 20) ? 1 : 0;
+    p.vfc.stream = p.vqkv.stream = p.vo.stream = p.vgu.stream = p.vdown.stream = stream;
+    p.vhead.stream = 1;
   }
   plan_gemm(p.head, dm.V + 3, D, B, 2, p.mfma, dm.V);
   p.head.n_extra = 3;

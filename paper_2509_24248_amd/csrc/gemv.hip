@@ -28,9 +28,20 @@ namespace {
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ uint4 load_stream16(const char* p) {
-  const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
-  return make_uint4(t.x, t.y, t.z, t.w);
+// The head's 778 MB are read once per launch and must not displace anything: non-temporal
+// loads.  The layer's projections come round again one draft step later; when they fit the 256 MB
+// last-level cache (228 MB at the metric's workload) ordinary loads let it keep part of them
+// (measured: 764 -> 775 rounds/s; with ordinary loads in the head as well, 696).  A layer that
+// does not fit is streamed like the head (ordinary loads cost 2 % there, measured on the
+// matrix-core projections of the 8B- and 32B-like shapes).
+template <bool STREAM>
+__device__ __forceinline__ uint4 load_weights16(const char* p) {
+  if constexpr (STREAM) {
+    const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(t.x, t.y, t.z, t.w);
+  } else {
+    return *reinterpret_cast<const uint4*>(p);
+  }
 }
 
 __device__ __forceinline__ const char* weight_row(const GemvArgs& g, int n) {
@@ -51,7 +62,7 @@ __device__ __forceinline__ int act_pos(int M, int m, int k) {
   return (((j * M + m) * 2 + (e >> 2)) * 64 + l) * 4 + (e & 3);
 }
 
-template <int MR, int SIF>
+template <int MR, int SIF, bool STREAM>
 __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
   extern __shared__ float lds[];
   __shared__ float rs_sh[4];
@@ -136,8 +147,8 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
       for (int u = 0; u < SIF; ++u) {
         const int j = j0 + u;
         const bool ok = j < steps;
-        w1[u] = ok ? load_stream16(r1 + (static_cast<size_t>(j) << 10)) : make_uint4(0, 0, 0, 0);
-        w2[u] = ok ? load_stream16(r2 + (static_cast<size_t>(j) << 10)) : make_uint4(0, 0, 0, 0);
+        w1[u] = ok ? load_weights16<STREAM>(r1 + (static_cast<size_t>(j) << 10)) : make_uint4(0, 0, 0, 0);
+        w2[u] = ok ? load_weights16<STREAM>(r2 + (static_cast<size_t>(j) << 10)) : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
       for (int u = 0; u < SIF; ++u) {
@@ -258,17 +269,17 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
   }
 }
 
-template <int MR, int SIF>
+template <int MR, int SIF, bool STREAM>
 hipError_t launch_mr_sif(const GemvArgs& g, hipStream_t s) {
   const size_t lds = gemv_lds_bytes(g);
   static bool attr_set = false;
   if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemv<MR, SIF>),
+    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemv<MR, SIF, STREAM>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL((k_gemv<MR, SIF>), dim3(g.grid), dim3(64 * g.waves), lds, s, g);
+  hipLaunchKernelGGL((k_gemv<MR, SIF, STREAM>), dim3(g.grid), dim3(64 * g.waves), lds, s, g);
   return hipGetLastError();
 }
 
@@ -276,7 +287,8 @@ hipError_t launch_mr_sif(const GemvArgs& g, hipStream_t s) {
 // (measured: 1, 3, 4, 5 slower, as are grids of 1, 3, 4, .. workgroups per compute unit).
 template <int MR>
 hipError_t launch_mr(const GemvArgs& g, hipStream_t s) {
-  return g.epi == 3 ? launch_mr_sif<MR, kHeadStepsInFlight>(g, s) : launch_mr_sif<MR, kStepsInFlight>(g, s);
+  if (g.epi == 3) return launch_mr_sif<MR, kHeadStepsInFlight, true>(g, s);
+  return g.stream ? launch_mr_sif<MR, kStepsInFlight, true>(g, s) : launch_mr_sif<MR, kStepsInFlight, false>(g, s);
 }
 
 }  // namespace

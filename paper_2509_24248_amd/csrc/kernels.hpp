@@ -118,6 +118,7 @@ struct GemvArgs {
   int* part_idx;
   float* extra_out;
   RopeArgs rope;
+  int stream;            // 1: weights read with non-temporal loads (read once; always for the head), 0: ordinary loads
   int grid, waves;       // launch shape, from gemv_plan
 };
 bool gemv_supported(int M, int N, int K);
