@@ -438,7 +438,7 @@ def main():
         "accepted_tokens_per_s": float(rnd.accept_len.float().sum().item() + shape.B) * 1000.0 / ms,
         "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
         "roofline": {"kernel": ("k_gemm_mfma<..,2,true> with the ranked-candidates epilogue" if shape.tree else
-                                f"k_gemv<{shape.B},2> with the head epilogue" if shape.B <= 4 and shape.dtype == "bf16" and shape.D % 512 == 0
+                                f"k_gemv<{shape.B},2,true> with the head epilogue" if shape.B <= 4 and shape.dtype == "bf16" and shape.D % 512 == 0
                                 else "k_gemm_mfma<..,2,true>") + " (widened-head GEMM + argmax of the draft step)",
                      "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(shape.name),
