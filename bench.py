@@ -4,10 +4,13 @@
 A "step" is one decode round: k x specexit_draft_step (chained), one
 specexit_verify_attn call (one target layer), one specexit_lmhead_argmax over the
 B*n_q block rows and one specexit_accept_exit.  Inputs are seeded synthetic tensors of
-the workload's shapes, resident in HBM before the timed region.  One JSON line is
-printed: rounds/s (value), draft tokens verified/s, the roofline of the dominant kernel
-(the widened-head weight-streaming GEMM of the draft step) measured live with HIP
-events, and the CPU oracle timed on the host cores as a baseline."""
+the workload's shapes, resident in HBM before the timed region.  The default workload is
+the largest configuration (32B-like shapes, 16 sequences, paged caches of 8k-32k entries).
+One JSON line is printed: rounds/s (value), draft tokens verified/s, the roofline of the
+kernel that takes the largest share of the round (durations measured live with HIP events
+the library records around its own launches; every other heavy kernel is listed beside it
+with its HBM and matrix-core fractions), and the CPU oracle timed on the host cores on a
+stated sample of the same workload."""
 from __future__ import annotations
 
 import argparse
@@ -22,14 +25,18 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0        # dense bf16
+RIDGE = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)   # FLOP per byte where the two rooflines meet
+DEFAULT_CONFIG = 4
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=1, help="index into the workload configurations (default: the metric's)")
+    ap.add_argument("--config", type=int, default=DEFAULT_CONFIG,
+                    help="index into the workload configurations (default: the largest one)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--seed", type=int, default=0)
@@ -230,28 +237,61 @@ def plant_acceptance(rnd: Round):
 
 
 def cpu_baseline(rnd: Round):
-    """The oracle, as it stands, on the same inputs: one full round on the host cores."""
+    """The oracle, as it stands, on the same inputs and the host cores.  Small workloads: one
+    full round.  Large ones: a stated sample of the round's parts, each scaled to the whole
+    (the oracle walks rows, queries and heads one by one, so its time is linear in them).
+    Returns (seconds per round, description of the sample)."""
     from oracle import specexit_oracle as O
     from workloads import gen
     s, h = rnd.shape, rnd.host
     store = lambda a: gen.store(s, a.astype(np.float32))
     dims = O.DraftDims(s.D, s.Hq, s.Hkv, s.d, s.V, s.rms_eps, s.rope_theta)
-    t0 = time.perf_counter()
-    kc, vc = h["dkv"].k.astype(np.float64), h["dkv"].v.astype(np.float64)
-    tok, g, sig0 = h["tok0"], h["g0"], None
-    for j in range(rnd.n_draft_steps):
-        out = O.draft_step(dims, h["w"], kc, vc, tok, g, rnd.L + j, h["dkv"].page_table if h["dkv"].paged else None,
-                           h["dkv"].page_size, store=store)
-        tok, g = out["next_tok"], store(out["hidden_out"])
-        sig0 = out["sig"] if sig0 is None else sig0
-    tk = h["tkv"]
-    O.verify_attn(h["q"], tk.k, tk.v, rnd.L, h["mask"], rnd.scale, tk.page_table if tk.paged else None, tk.page_size)
-    am, _, _ = O.lmhead_argmax(h["hid"], h["lm"])
     c = h["case"]
+    dkv, tk = h["dkv"], h["tkv"]
+    if s.index <= 1:
+        t0 = time.perf_counter()
+        kc, vc = dkv.k.astype(np.float64), dkv.v.astype(np.float64)
+        tok, g, sig0 = h["tok0"], h["g0"], None
+        for j in range(rnd.n_draft_steps):
+            out = O.draft_step(dims, h["w"], kc, vc, tok, g, rnd.L + j, dkv.page_table if dkv.paged else None,
+                               dkv.page_size, store=store)
+            tok, g = out["next_tok"], store(out["hidden_out"])
+            sig0 = out["sig"] if sig0 is None else sig0
+        O.verify_attn(h["q"], tk.k, tk.v, rnd.L, h["mask"], rnd.scale, tk.page_table if tk.paged else None, tk.page_size)
+        am, _, _ = O.lmhead_argmax(h["hid"], h["lm"])
+        O.accept_exit(O.ExitCfg(stop_think_token=c.stop_think_token), c.block_tok, h["parent"],
+                      am.reshape(s.B, s.n_q), sig0, rnd.L, c.split_tok, np.zeros((s.B, 3)), np.zeros(s.B, np.int32),
+                      np.ones(s.B, np.int32))
+        sec = time.perf_counter() - t0
+        return sec, f"one full round of the same workload and inputs ({sec:.1f} s of numpy float64)"
+    # ---- draft forward: the first row of the first step (the cache is read in place: float32 values
+    # of the storage type; the row's own entry is written into it)
+    t0 = time.perf_counter()
+    out = O.draft_step(dims, h["w"], dkv.k, dkv.v, h["tok0"][:1], h["g0"][:1], rnd.L[:1],
+                       dkv.page_table if dkv.paged else None, dkv.page_size, store=store)
+    t_row = time.perf_counter() - t0
+    n_rows = s.B * (sum(lv["W"] for lv in rnd.levels) if s.tree else rnd.n_draft_steps)
+    # ---- verification attention: a sample of (sequence, query, head) outputs, scaled by visible keys
+    r = np.random.default_rng(7)
+    only = [(int(r.integers(s.B)), int(r.integers(s.n_q)), int(r.integers(s.Hq))) for _ in range(32)]
+    t0 = time.perf_counter()
+    O.verify_attn(h["q"], tk.k, tk.v, rnd.L, h["mask"], rnd.scale, tk.page_table if tk.paged else None, tk.page_size, only)
+    t_attn_s = time.perf_counter() - t0
+    keys_all = float((rnd.L.astype(np.int64) + s.n_q).sum()) * s.n_q * s.Hq
+    keys_s = float(sum(int(rnd.L[b]) + s.n_q for b, _, _ in only))
+    # ---- LM head over all block rows, acceptance and exit rule over all sequences
+    t0 = time.perf_counter()
+    am, _, _ = O.lmhead_argmax(h["hid"], h["lm"])
     O.accept_exit(O.ExitCfg(stop_think_token=c.stop_think_token), c.block_tok, h["parent"],
-                  am.reshape(s.B, s.n_q), sig0, rnd.L, c.split_tok, np.zeros((s.B, 3)), np.zeros(s.B, np.int32),
-                  np.ones(s.B, np.int32))
-    return time.perf_counter() - t0
+                  am.reshape(s.B, s.n_q), out["sig"].repeat(s.B, axis=0), rnd.L, c.split_tok, np.zeros((s.B, 3)),
+                  np.zeros(s.B, np.int32), np.ones(s.B, np.int32))
+    t_head = time.perf_counter() - t0
+    sec = t_row * n_rows + t_attn_s * keys_all / keys_s + t_head
+    what = (f"measured {t_row + t_attn_s + t_head:.1f} s of numpy float64: 1 of the {n_rows} draft-forward rows of the round "
+            f"({t_row:.1f} s, scaled by {n_rows}), 32 of the {s.B * s.n_q * s.Hq} verification-attention outputs "
+            f"({t_attn_s:.1f} s, scaled by visible keys x{keys_all / keys_s:.0f}), the whole LM head and accept/exit ({t_head:.1f} s); "
+            f"extrapolated round: {sec:.0f} s")
+    return sec, what
 
 
 def threads_used():
@@ -265,9 +305,10 @@ def threads_used():
     return int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
 
 
-def stored_traffic(shape_name):
-    """HBM bytes per launch of the dominant kernel from the committed counter summary, if present."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_head_gemm_{shape_name}.txt")
+def stored_traffic(kernel_key, shape_name):
+    """HBM bytes per launch of a kernel from the committed counter summary (FETCH_SIZE + WRITE_SIZE
+    runs of this same command, scaled by the copy probe), if present."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{kernel_key}_{shape_name}.txt")
     try:
         with open(path) as fh:
             for line in fh:
@@ -276,6 +317,16 @@ def stored_traffic(shape_name):
     except Exception:
         pass
     return None
+
+
+def round_bytes(shape, rnd, n_steps, rows, draft_keys, keys_ctx):
+    """Algorithmic HBM bytes of one round: per draft launch the layer's and the head's weights and the
+    draft cache; once the target layer's cache and the LM head."""
+    e = 2 if shape.dtype == "bf16" else 4
+    D, Hd, Hk, I, V = shape.D, shape.Hq * shape.d, shape.Hkv * shape.d, shape.I, shape.V
+    layer = e * (2 * D * D + D * Hd + 2 * D * Hk + Hd * D + 3 * D * I)
+    per_step = layer + e * (V + 3) * D + 2 * e * shape.Hkv * shape.d * draft_keys
+    return n_steps * per_step + 2 * e * shape.Hkv * shape.d * (keys_ctx + shape.B * shape.n_q) + e * V * D
 
 
 def main():
@@ -289,7 +340,7 @@ def main():
     assert torch.cuda.is_available(), "a GPU is required"
     torch.cuda.set_device(0)
     shape = gen.config(args.config)
-    want_cpu = not args.no_cpu_baseline and args.config <= 1
+    want_cpu = not args.no_cpu_baseline
     rnd = Round(shape, args.seed, keep_host=want_cpu)
     stream = torch.cuda.current_stream()
 
@@ -306,19 +357,21 @@ def main():
         torch.cuda.synchronize()
         del dst
 
-    # ---- eager leg with per-kernel events: duration of the dominant kernel, live
+    # ---- eager leg with per-kernel events: durations of the heavy kernels, live
     K = args.steps
-    n_ev = K * rnd.n_draft_steps
+    n_steps = rnd.n_draft_steps if rnd.levels is None else len(rnd.levels)
     mk = lambda n: [torch.cuda.Event(enable_timing=True) for _ in range(n)]
-    ev0, ev1 = mk(n_ev), mk(n_ev)
-    lm0, lm1 = mk(K), mk(K)
-    at0, at1 = mk(K), mk(K)
-    for e in ev0 + ev1 + lm0 + lm1 + at0 + at1:
-        e.record(stream)                                    # creates the underlying handles
+    prof = {"draft_head_gemm": (sx.PROF_DRAFT_HEAD_GEMM, K * n_steps), "draft_attn_split": (sx.PROF_DRAFT_ATTN, K * n_steps),
+            "lmhead_gemm": (sx.PROF_LMHEAD_GEMM, K), "verify_attn_split": (sx.PROF_VERIFY_ATTN, K)}
+    evs = {}
+    for name, (kid, n) in prof.items():
+        e0, e1 = mk(n), mk(n)
+        for e in e0 + e1:
+            e.record(stream)                                # creates the underlying handles
+        evs[name] = (e0, e1)
     torch.cuda.synchronize()
-    sx.specexit_profile_events(sx.PROF_DRAFT_HEAD_GEMM, ev0, ev1)
-    sx.specexit_profile_events(sx.PROF_LMHEAD_GEMM, lm0, lm1)
-    sx.specexit_profile_events(sx.PROF_VERIFY_ATTN, at0, at1)
+    for name, (kid, n) in prof.items():
+        sx.specexit_profile_events(kid, *evs[name])
     e_start, e_stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e_start.record(stream)
@@ -327,11 +380,12 @@ def main():
     e_stop.record(stream)
     torch.cuda.synchronize()
     eager_ms = e_start.elapsed_time(e_stop) / K
-    for kid in (sx.PROF_DRAFT_HEAD_GEMM, sx.PROF_LMHEAD_GEMM, sx.PROF_VERIFY_ATTN):
+    kernel_ms = {}
+    for name, (kid, n) in prof.items():
+        used = sx.specexit_profile_events_used(kid)
         sx.specexit_profile_events(kid)
-    head_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(ev0, ev1)]))
-    lm_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(lm0, lm1)]))
-    attn_ms = float(np.mean([a.elapsed_time(b) for a, b in zip(at0, at1)]))
+        assert used == n, f"{name}: {used} of {n} event pairs were recorded"
+        kernel_ms[name] = float(np.mean([a.elapsed_time(b) for a, b in zip(*evs[name])]))
 
     # ---- timed region for `value`: K rounds, replayed from a HIP graph unless --no-graph
     graph_ms = None
@@ -416,11 +470,43 @@ def main():
         calls["tree drafting, all levels (draft_tree_level + tree_gather)"] = per_call(rnd.draft_tree)
     n_layers = {"tiny_f32": 4, "qwen3_4b_chain": 36, "qwen3_8b_paged": 36, "tree_8b": 36, "qwen3_32b_paged": 64}[shape.name]
 
+    # ---- algorithmic bytes and FLOPs per launch of the heavy kernels
     e = 2 if shape.dtype == "bf16" else 4
-    head_bytes = e * (shape.V + 3) * shape.D + e * 2 * shape.B * shape.D + 8 * shape.B * ((shape.V + 18) // 16)
-    lm_bytes = e * shape.V * shape.D + e * shape.B * shape.n_q * shape.D
-    kv_bytes = 2 * e * shape.Hkv * shape.d * int((rnd.L + shape.n_q).sum()) + 2 * e * shape.B * shape.n_q * shape.Hq * shape.d
-    achieved = head_bytes / (head_ms * 1e-3) / 1e9
+    rows = shape.B if rnd.levels is None else float(np.mean([lv["W"] for lv in rnd.levels])) * shape.B   # draft rows per launch
+    keys_ctx = int(rnd.L.astype(np.int64).sum())
+    pages = lambda extra: int(sum(-(-(int(l) + extra) // shape.page_size) for l in rnd.L)) if shape.paged else 0
+    draft_keys = keys_ctx + shape.B * ((n_steps + 1) / 2.0 if rnd.levels is None else shape.n_q / 2.0)   # mean over the steps
+    spec = {
+        # weights once + fp32 rows in, bf16 rows out + one (value, index) candidate per 16-row tile
+        "draft_head_gemm": dict(bytes=e * (shape.V + 3) * shape.D + e * 2 * rows * shape.D + 8 * rows * ((shape.V + 18) // 16),
+                                flops=2.0 * rows * (shape.V + 3) * shape.D, launches=n_steps,
+                                what="widened-head GEMM + argmax of the draft step"),
+        # K and V of every cache entry once + q in, out out + page ids
+        "draft_attn_split": dict(bytes=2 * e * shape.Hkv * shape.d * draft_keys + 2 * e * rows * shape.Hq * shape.d + 4 * pages(n_steps),
+                                 flops=4.0 * (rows / shape.B) * shape.Hq * shape.d * draft_keys, launches=n_steps,
+                                 what="split-KV attention of the draft layer over its own cache"),
+        "lmhead_gemm": dict(bytes=e * shape.V * shape.D + e * shape.B * shape.n_q * shape.D + 8 * shape.B * shape.n_q * ((shape.V + 15) // 16),
+                            flops=2.0 * shape.B * shape.n_q * shape.D * shape.V, launches=1,
+                            what="target LM-head GEMM + argmax over the block rows"),
+        "verify_attn_split": dict(bytes=2 * e * shape.Hkv * shape.d * (keys_ctx + shape.B * shape.n_q) + 2 * e * shape.B * shape.n_q * shape.Hq * shape.d + 4 * pages(shape.n_q),
+                                  flops=4.0 * shape.n_q * shape.Hq * shape.d * (keys_ctx + shape.B * shape.n_q), launches=1,
+                                  what="split-KV verification attention of one target layer"),
+    }
+    kernels = {}
+    for name, sp in spec.items():
+        ms_k = kernel_ms[name]
+        gbs = sp["bytes"] / (ms_k * 1e-3) / 1e9
+        tfl = sp["flops"] / (ms_k * 1e-3) / 1e12
+        ai = sp["flops"] / sp["bytes"]
+        kernels[name] = {"what": sp["what"], "avg_launch_ms": ms_k, "launches_per_round": sp["launches"],
+                         "share_of_round": ms_k * sp["launches"] / eager_ms,
+                         "bytes_per_launch": int(sp["bytes"]), "achieved_GBs": gbs, "frac_hbm_peak": gbs / HBM_PEAK_GBS,
+                         "flops_per_launch": sp["flops"], "achieved_TFLOPs": tfl, "frac_mfma_bf16_peak": tfl / MFMA_BF16_PEAK_TFLOPS,
+                         # the most the matrix cores can be used while the weights / cache stream at HBM peak
+                         "mfma_ceiling_at_hbm_peak": min(1.0, ai / RIDGE),
+                         "traffic_bytes_per_launch": stored_traffic(name, shape.name)}
+    top = max(kernels, key=lambda n: kernels[n]["share_of_round"])
+    kt = kernels[top]
     out = {
         "metric": "verify rounds/sec (and draft tokens verified/sec) per MI355X",
         "value": 1000.0 / ms,
@@ -437,15 +523,14 @@ def main():
         # tokens the planted acceptance pattern yields per round: accepted drafts + the recover token
         "accepted_tokens_per_s": float(rnd.accept_len.float().sum().item() + shape.B) * 1000.0 / ms,
         "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
-        "roofline": {"kernel": ("k_gemm_mfma<..,2,true> with the ranked-candidates epilogue" if shape.tree else
-                                f"k_gemv<{shape.B},2,true> with the head epilogue" if shape.B <= 4 and shape.dtype == "bf16" and shape.D % 512 == 0
-                                else "k_gemm_mfma<..,2,true>") + " (widened-head GEMM + argmax of the draft step)",
-                     "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": stored_traffic(shape.name),
-                     "bytes_per_launch": head_bytes, "avg_launch_ms": head_ms},
-        "other_kernels": {
-            "lmhead_gemm": {"avg_launch_ms": lm_ms, "achieved_GBs": lm_bytes / (lm_ms * 1e-3) / 1e9, "bytes": lm_bytes},
-            "verify_attn_split": {"avg_launch_ms": attn_ms, "achieved_GBs": kv_bytes / (attn_ms * 1e-3) / 1e9, "bytes": kv_bytes}},
+        "round_bytes": {"what": "algorithmic HBM bytes of the whole round (draft layers, heads, both caches) over its time",
+                        "bytes": int(round_bytes(shape, rnd, n_steps, rows, draft_keys, keys_ctx)),
+                        "achieved_GBs": round_bytes(shape, rnd, n_steps, rows, draft_keys, keys_ctx) / (ms * 1e-3) / 1e9},
+        "roofline": {"kernel": f"{top}: {kt['what']} ({kt['share_of_round'] * 100:.0f} % of the round's time)",
+                     "bound": "hbm", "achieved": kt["achieved_GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": kt["frac_hbm_peak"], "traffic": kt["traffic_bytes_per_launch"],
+                     "bytes_per_launch": kt["bytes_per_launch"], "avg_launch_ms": kt["avg_launch_ms"]},
+        "kernels": kernels,
         "eager_ms_per_call": calls,
         "per_call_note": f"back-to-back calls of one export; verify_attn cycles through {n_copies} copies of the KV cache "
                          f"({n_copies * kv_alloc / 1e6:.0f} MB in all)" +
@@ -456,9 +541,9 @@ def main():
                        "verify_attn_ms_all_layers": calls["specexit_verify_attn"] * n_layers},
     }
     if want_cpu:
-        sec = cpu_baseline(rnd)
+        sec, what = cpu_baseline(rnd)
         out["cpu_baseline"] = {"value": 1.0 / sec, "unit": "rounds/s", "cores": threads_used(), "kind": "oracle",
-                               "sample": f"one full round of the same workload and inputs ({sec:.1f} s of numpy float64)"}
+                               "sample": what}
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))

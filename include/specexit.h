@@ -19,8 +19,11 @@
  *     the matching *_workspace_bytes() query says.  Its contents are undefined afterwards.
  *   - Return value: SPECEXIT_OK or a negative error code; specexit_last_error() then
  *     returns a thread-local description.  No kernel is launched when validation fails.
- *   - Contents of device arrays (token ids, page indices, lengths) are trusted: ids and
- *     page numbers out of range are undefined behaviour.
+ *   - Contents of device arrays never reach an address unchecked: context lengths, cache
+ *     positions, page ids, token ids and node ids are forced into their valid range before use,
+ *     so a bad value gives a wrong result for its sequence or row and never a memory fault.
+ *     With SPECEXIT_FLAG_VALIDATE in `flags` the first such value seen by a call's kernels is
+ *     also reported in the device status word registered with specexit_set_dev_status.
  *   - dtype selects the storage type of weights, KV caches, q, hidden states and the
  *     attention output (SPECEXIT_F32 or SPECEXIT_BF16).  Accumulation, softmax, norms and
  *     activations are always fp32.  All matrices are row-major [out, in].
@@ -52,9 +55,24 @@ typedef enum { SPECEXIT_KV_CONTIG = 0, SPECEXIT_KV_PAGED = 1 } specexit_kv_layou
  * that same entry point with the same descriptor, cache view and row counts.  The call then
  * skips the launch that clears its arrival counters (every kernel leaves them at zero). */
 #define SPECEXIT_FLAG_WORKSPACE_PREPARED 1u
+/* flags bit: report out-of-range device data.  The kernels of the call write the first problem
+ * they see into the status word of the calling host thread (specexit_set_dev_status), if that
+ * word is still 0: SPECEXIT_STATUS_*.  The call itself still returns SPECEXIT_OK (it does not
+ * wait for its kernels); the caller reads the word when it synchronises, and zeroes it. */
+#define SPECEXIT_FLAG_VALIDATE 2u
+#define SPECEXIT_STATUS_OK         0
+#define SPECEXIT_STATUS_BAD_LENGTH 1 /* ctx_len / pos negative or beyond the cache capacity       */
+#define SPECEXIT_STATUS_BAD_PAGE   2 /* page id outside 0 .. n_pages-1                            */
+#define SPECEXIT_STATUS_BAD_TOKEN  3 /* token id outside 0 .. vocab-1                             */
+#define SPECEXIT_STATUS_BAD_NODE   4 /* node id / path entry outside its block                    */
 #define SPECEXIT_MAX_NQ 64
 #define SPECEXIT_MAX_TOP_B 4 /* ranked continuations a tree-drafting row can report */
 #define SPECEXIT_N_SIGNALS 3
+
+/* Registers (dev_status != NULL) or clears (NULL) the device int32 that calls made by THIS host
+ * thread with SPECEXIT_FLAG_VALIDATE report into.  [host] call; the word itself is device memory
+ * owned by the caller, zeroed by the caller, and must stay valid while such calls are in flight. */
+int32_t specexit_set_dev_status(int32_t *dev_status);
 
 /* Draft model dimensions (the draft layer mirrors the target's attention geometry). */
 typedef struct {
@@ -168,8 +186,9 @@ int32_t specexit_graph_destroy(specexit_graph *graph);
 /* Zero-fills a workspace (a small kernel on `stream`; see SPECEXIT_FLAG_WORKSPACE_PREPARED). */
 int32_t specexit_workspace_prepare(void *workspace, size_t workspace_bytes, void *stream);
 
-/* ---- stage 1 over a tree: one level of tree drafting (the block "forward through M_t with
- * tree attention" of Alg. 1 verifies; the draft forward is that of specexit_draft_step) ----
+/* ---- stage 1 over a tree: one level of tree drafting (it builds the candidate block that the
+ * target's verification forward of Alg. 1 checks; the draft forward is that of
+ * specexit_draft_step) ----
  * The candidate tree has a fixed topology: node 0 is the last accepted token, node c > 0 holds
  * the rank[c]-th most likely continuation (0 = argmax) of its parent.  A level call runs the
  * draft forward for W nodes of equal depth `level` of each of the B sequences (rows ordered
@@ -210,7 +229,8 @@ int32_t specexit_tree_gather(int32_t dtype, int32_t B, int32_t W_prev, int32_t t
                              void *hidden_next /*[B,W_next,D] or NULL*/, int32_t *block_tok /*[B,n_q] or NULL*/,
                              uint32_t flags, void *stream);
 
-/* ---- stage 2: verification attention (Alg. 1, "forward through M_t with tree attention") ----
+/* ---- stage 2: verification attention (Alg. 1, target verification step: the block's queries
+ * under a chain or tree-ancestor mask) ----
  * out[b,i,h,:] = sum_j softmax_j(scale * q[b,i,h,:] . K[j]) V[j] over the visible cache
  * positions j of query i: the context 0..ctx_len[b]-1 plus the block entries
  * ctx_len[b]+t whose bit t is set in mask[b,i] (mask NULL = chain: bits 0..i).  The
@@ -225,7 +245,8 @@ int32_t specexit_verify_attn(const specexit_kv_view *kv, int32_t B, int32_t n_q,
 size_t specexit_verify_attn_workspace_bytes(const specexit_kv_view *kv, int32_t B, int32_t n_q,
                                             int32_t n_q_heads);
 
-/* ---- stage 3: LM head -> argmax (Alg. 1, "target model recover token"; greedy) ----
+/* ---- stage 3: LM head -> argmax (Alg. 1, the target's own next tokens that acceptance compares
+ * against and recovers from; greedy) ----
  * z = hidden . w^T with w [V + n_extra, D]; argmax[r] = lowest index of the maximum of
  * z[r, 0:V].  Rows V.. of w (the widened head's signal rows, Eq. 1) never enter the
  * argmax; their products go to extra_out [M, n_extra].  max_logit, extra_out and
@@ -272,8 +293,8 @@ int32_t specexit_accept_exit(const specexit_exit_cfg *cfg, int32_t B, int32_t n_
                              int32_t *exit_flag /*[B]*/, int32_t *new_ctx_len /*[B]*/,
                              uint32_t flags, void *stream);
 
-/* ---- after the round: cache compaction (Alg. 1, "update KV-cache and hidden states
- * accordingly") ----
+/* ---- after the round: cache compaction (Alg. 1, cache-update step inside the exit branch,
+ * applied after every round) ----
  * Per sequence b, with L = ctx_len[b] (the value the round started with) and the outputs of
  * specexit_accept_exit: the K/V entry of accepted node accept_path[b,j], stored at cache
  * position L + accept_path[b,j] during verification, moves to position L + 1 + j for
@@ -298,7 +319,8 @@ int32_t specexit_kv_compact(const specexit_kv_view *kv, int32_t n_layers, int64_
  * on, each launch of the named kernel records the next unused pair around that one kernel on
  * the call's stream (start before, stop after), until the pairs run out; n = 0 disarms.
  * Returns the number of pairs consumed so far for that kernel when called with n < 0.
- * Not thread-safe; do not arm while a stream is being captured into a graph. */
+ * Arming and recording are serialised by a lock; do not arm while a stream is being captured
+ * into a graph. */
 #define SPECEXIT_PROF_DRAFT_HEAD_GEMM 0 /* widened-head GEMM + argmax inside specexit_draft_step */
 #define SPECEXIT_PROF_LMHEAD_GEMM     1 /* GEMM + argmax inside specexit_lmhead_argmax            */
 #define SPECEXIT_PROF_VERIFY_ATTN     2 /* split-KV kernel inside specexit_verify_attn            */
@@ -311,6 +333,34 @@ int32_t specexit_profile_events(int32_t kernel, void *const *start_events, void 
  * != 0, ordinary ones otherwise.  A plain kernel of known traffic: profiler byte counters
  * read for the library's kernels are scaled by what they read for this one. */
 int32_t specexit_copy_probe(const void *src, void *dst, size_t bytes, int32_t nontemporal, void *stream);
+
+/* ---- scratch sizes, one query for every call ------------------------------------------------
+ * Bytes of workspace that call `op` needs for B sequences and n_q block entries (draft tree level:
+ * n_q = W rows per sequence; LM head: M = B * n_q rows).  `desc` is a [host] struct of the op's
+ * query type below (first field struct_size); 0 is returned for shapes the call would reject and
+ * for ops that use no scratch.  The per-call *_workspace_bytes functions give the same numbers. */
+#define SPECEXIT_OP_DRAFT_STEP       0 /* desc: specexit_draft_query                        */
+#define SPECEXIT_OP_VERIFY_ATTN      1 /* desc: specexit_attn_query                         */
+#define SPECEXIT_OP_LMHEAD_ARGMAX    2 /* desc: specexit_lmhead_query                       */
+#define SPECEXIT_OP_ACCEPT_EXIT      3 /* no scratch: 0                                     */
+#define SPECEXIT_OP_DRAFT_TREE_LEVEL 4 /* desc: specexit_draft_query (top_b used)           */
+#define SPECEXIT_OP_KV_COMPACT       5 /* no scratch: 0                                     */
+typedef struct {
+  uint32_t struct_size;
+  const specexit_model_desc *desc;
+  const specexit_kv_view *draft_kv;
+  int32_t top_b; /* tree level only */
+} specexit_draft_query;
+typedef struct {
+  uint32_t struct_size;
+  const specexit_kv_view *kv;
+  int32_t n_q_heads;
+} specexit_attn_query;
+typedef struct {
+  uint32_t struct_size;
+  int32_t dtype, hidden, vocab, n_extra;
+} specexit_lmhead_query;
+size_t specexit_workspace_bytes(int32_t op, const void *desc, int32_t B, int32_t n_q);
 
 const char *specexit_last_error(void); /* [host] thread-local, never NULL */
 uint32_t specexit_version(void);

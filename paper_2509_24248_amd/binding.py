@@ -27,11 +27,15 @@ EXPORTS = [
     "specexit_draft_tree_level", "specexit_draft_tree_level_workspace_bytes", "specexit_tree_gather",
     "specexit_graph_begin", "specexit_graph_end", "specexit_graph_launch", "specexit_graph_destroy",
     "specexit_workspace_prepare", "specexit_accept_exit", "specexit_kv_compact", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
+    "specexit_workspace_bytes", "specexit_set_dev_status",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
 SMOOTH_EWMA, SMOOTH_NONE, SMOOTH_WINDOW, SMOOTH_MOMENTUM, SMOOTH_PARAGRAPH = 0, 1, 2, 3, 4
 SMOOTH_WORDS = 48
 FLAG_WORKSPACE_PREPARED = 1
+FLAG_VALIDATE = 2
+STATUS_OK, STATUS_BAD_LENGTH, STATUS_BAD_PAGE, STATUS_BAD_TOKEN, STATUS_BAD_NODE = 0, 1, 2, 3, 4
+OP_DRAFT_STEP, OP_VERIFY_ATTN, OP_LMHEAD_ARGMAX, OP_ACCEPT_EXIT, OP_DRAFT_TREE_LEVEL, OP_KV_COMPACT = 0, 1, 2, 3, 4, 5
 
 
 class SpecExitError(RuntimeError):
@@ -67,6 +71,20 @@ class ExitCfg(C.Structure):
                 ("thr_prog", C.c_float), ("thr_rem", C.c_float), ("signal_mask", C.c_uint32),
                 ("smoother", C.c_int32), ("split_pick", C.c_int32), ("check_root", C.c_int32),
                 ("stop_think_token", C.c_int32), ("window", C.c_int32)]
+
+
+class DraftQuery(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("desc", C.POINTER(ModelDesc)), ("draft_kv", C.POINTER(KVView)),
+                ("top_b", C.c_int32)]
+
+
+class AttnQuery(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("kv", C.POINTER(KVView)), ("n_q_heads", C.c_int32)]
+
+
+class LmHeadQuery(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("dtype", C.c_int32), ("hidden", C.c_int32), ("vocab", C.c_int32),
+                ("n_extra", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -116,6 +134,10 @@ def _load() -> C.CDLL:
     lib.specexit_copy_probe.argtypes = [vp, vp, sz, i32, vp]
     lib.specexit_profile_events.restype = i32
     lib.specexit_profile_events.argtypes = [i32, C.POINTER(vp), C.POINTER(vp), i32]
+    lib.specexit_workspace_bytes.restype = sz
+    lib.specexit_workspace_bytes.argtypes = [i32, vp, i32, i32]
+    lib.specexit_set_dev_status.restype = i32
+    lib.specexit_set_dev_status.argtypes = [vp]
     return lib
 
 
@@ -330,3 +352,32 @@ def specexit_profile_events_used(kernel: int) -> int:
 
 def specexit_copy_probe(src, dst, nbytes: int, nontemporal: bool, stream=None) -> None:
     _check(LIB.specexit_copy_probe(_ptr(src), _ptr(dst), nbytes, 1 if nontemporal else 0, _stream(stream)))
+
+
+def specexit_workspace_bytes(op: int, desc, B: int, n_q: int) -> int:
+    """desc: a DraftQuery / AttnQuery / LmHeadQuery (see draft_query, attn_query, lmhead_query) or None."""
+    return int(LIB.specexit_workspace_bytes(op, None if desc is None else C.cast(C.byref(desc), C.c_void_p), B, n_q))
+
+
+def draft_query(desc: ModelDesc, draft_kv: KVView, top_b: int = 1) -> DraftQuery:
+    q = DraftQuery(C.sizeof(DraftQuery), C.pointer(desc), C.pointer(draft_kv), top_b)
+    q._keep = (desc, draft_kv)
+    return q
+
+
+def attn_query(kv: KVView, n_q_heads: int) -> AttnQuery:
+    q = AttnQuery(C.sizeof(AttnQuery), C.pointer(kv), n_q_heads)
+    q._keep = kv
+    return q
+
+
+def lmhead_query(dtype: int, hidden: int, vocab: int, n_extra: int = 0) -> LmHeadQuery:
+    return LmHeadQuery(C.sizeof(LmHeadQuery), dtype, hidden, vocab, n_extra)
+
+
+def specexit_set_dev_status(word: Optional[torch.Tensor]) -> None:
+    """word: a one-element int32 device tensor that calls with FLAG_VALIDATE made by this thread
+    report into (kept alive by the caller), or None to clear the registration."""
+    if word is not None:
+        assert word.is_cuda and word.dtype == torch.int32 and word.numel() >= 1
+    _check(LIB.specexit_set_dev_status(None if word is None else C.c_void_p(word.data_ptr())))

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(64) void k_accept_exit(const ExitArgs a) {
   for (int j = 0; j < 3; ++j) x[j] = a.ewma[b * 3 + j];
   float* hist = a.smooth_state ? a.smooth_state + static_cast<size_t>(b) * kSmoothWords : nullptr;
   if (thinking) {
-    const int seen = a.n_obs[b];
+    const int seen = max(a.n_obs[b], 0);   // caller-owned state: a negative count must not reach the ring index
     const int N = a.window;
     const int n = min(seen + 1, N);
     int par_count = 0;

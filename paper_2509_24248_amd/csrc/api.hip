@@ -2,12 +2,15 @@
 // order of kernel launches.  No arithmetic of the method lives here.
 #include "../../include/specexit.h"
 
+#include "common.hpp"
 #include "kernels.hpp"
 
 #include <stdarg.h>
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
+#include <mutex>
 #include <vector>
 
 using namespace sx;
@@ -30,16 +33,23 @@ int32_t check_hip(hipError_t e, const char* what) {
 }
 
 int num_cus() {
-  static int n = 0;
-  if (n == 0) {
-    int dev = 0;
+  // queried once per process (function-local static: initialised under the language's own lock)
+  static const int n = [] {
+    int dev = 0, cus = 0;
     hipDeviceProp_t p;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess)
-      n = p.multiProcessorCount;
-    if (n <= 0) n = 256;
-  }
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&p, dev) == hipSuccess) cus = p.multiProcessorCount;
+    return cus > 0 ? cus : 256;
+  }();
   return n;
 }
+
+// device status word of this host thread (specexit_set_dev_status); used by calls that pass
+// SPECEXIT_FLAG_VALIDATE
+static_assert(kStatusBadLength == SPECEXIT_STATUS_BAD_LENGTH && kStatusBadPage == SPECEXIT_STATUS_BAD_PAGE &&
+              kStatusBadToken == SPECEXIT_STATUS_BAD_TOKEN && kStatusBadNode == SPECEXIT_STATUS_BAD_NODE,
+              "status codes of the ABI and of the kernels differ");
+thread_local int32_t* g_dev_status = nullptr;
+int* status_for(uint32_t flags) { return (flags & SPECEXIT_FLAG_VALIDATE) ? g_dev_status : nullptr; }
 
 // caller-provided event pairs recorded around single kernels (measurement aid)
 struct ProfSlot {
@@ -47,13 +57,17 @@ struct ProfSlot {
   size_t used = 0;
 };
 ProfSlot g_prof[4];
+std::mutex g_prof_mu;   // arming and recording may come from different host threads
 
 struct ProfScope {
   ProfSlot* slot;
   hipStream_t s;
   bool on;
-  ProfScope(int id, hipStream_t st) : slot(&g_prof[id]), s(st), on(slot->used < slot->start.size()) {
+  std::unique_lock<std::mutex> lock;
+  ProfScope(int id, hipStream_t st) : slot(&g_prof[id]), s(st), lock(g_prof_mu) {
+    on = slot->used < slot->start.size();
     if (on) (void)hipEventRecord(slot->start[slot->used], s);
+    else lock.unlock();
   }
   ~ProfScope() {
     if (on) {
@@ -64,6 +78,7 @@ struct ProfScope {
 };
 
 void g_prof_hook(int id, int phase, hipStream_t s) {
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   ProfSlot& sl = g_prof[id];
   if (sl.used >= sl.start.size()) return;
   if (phase == 0) {
@@ -115,6 +130,7 @@ int32_t fill_attn(AttnArgs& a, const specexit_kv_view* kv, int32_t B, int32_t n_
   if (n_q < 1 || n_q > SPECEXIT_MAX_NQ) return fail(SPECEXIT_EINVAL, "%s: n_q %d outside 1..64", who, n_q);
   if (n_q_heads < 1 || n_q_heads % kv->n_kv_heads) return fail(SPECEXIT_EINVAL, "%s: n_q_heads %d is not a multiple of n_kv_heads %d", who, n_q_heads, kv->n_kv_heads);
   if ((n_q_heads / kv->n_kv_heads) * n_q > 128) return fail(SPECEXIT_EUNSUPPORTED, "%s: more than 128 query rows per KV head", who);
+  if (B > 1024) return fail(SPECEXIT_EUNSUPPORTED, "%s: more than 1024 sequences in one call", who);
   memset(&a, 0, sizeof(a));
   a.dtype = kv->dtype;
   a.paged = kv->layout == SPECEXIT_KV_PAGED;
@@ -131,7 +147,9 @@ int32_t fill_attn(AttnArgs& a, const specexit_kv_view* kv, int32_t B, int32_t n_
   a.Hq = n_q_heads;
   a.Hkv = kv->n_kv_heads;
   a.d = kv->head_dim;
-  attn_plan(a, num_cus());
+  a.n_pages = a.paged ? kv->n_pages : 0;
+  if (a.l_max < n_q) return fail(SPECEXIT_EINVAL, "%s: the cache holds %lld entries per sequence, fewer than the block's %d", who, static_cast<long long>(a.l_max), n_q);
+  if (!attn_plan(a, num_cus())) return fail(SPECEXIT_EUNSUPPORTED, "%s: %d sequences x %d KV heads x %lld cache entries is more than one call can split", who, B, a.Hkv, static_cast<long long>(a.l_max));
   return SPECEXIT_OK;
 }
 
@@ -339,6 +357,7 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
   const DraftDims& dm = p.dm;
   const bool bf16 = dm.dtype == SPECEXIT_BF16;
   const bool mf = p.mfma;
+  int* const status = status_for(io.flags);
 
   const int gd = gemm_groups(dm.D);
   if (p.gemv) {
@@ -352,6 +371,7 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     };
     GemvArgs g = p.vfc;                       // x = W_fc [embed[tok] ; hidden_in]
     g.w[0] = w->w_fc; g.a_mode = 2; g.a_src = io.hidden_in; g.a_embed = w->embed; g.a_tok = io.tok;
+    g.a_vocab = dm.V; g.status = status;
     g.out_x = b.x_buf; g.out_ssq = ssq_of(0);
     if ((rc = check_hip(launch_gemv(g, s), "gemv fc"))) return rc;
     g = p.vqkv;                               // q, k, v with rotary embedding, cache write
@@ -365,6 +385,7 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
       ra.Hq = dm.Hq; ra.Hkv = dm.Hkv; ra.d = dm.d; ra.q_out = b.q_buf; ra.paged = p.attn.paged;
       ra.kc = draft_kv->k; ra.vc = draft_kv->v; ra.page_table = draft_kv->page_table;
       ra.page_size = p.attn.page_size; ra.max_pages = p.attn.max_pages; ra.l_max = p.attn.l_max;
+      ra.n_pages = p.attn.n_pages; ra.status = status;
     }
     if ((rc = check_hip(launch_gemv(g, s), "gemv qkv"))) return rc;
   } else if (mf) {
@@ -397,6 +418,8 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     p.fc.a_src = io.hidden_in;
     p.fc.a_embed = w->embed;
     p.fc.a_tok = io.tok;
+    p.fc.a_vocab = dm.V;
+    p.fc.status = status;
     reducing(p.fc, 0, nullptr, b.x_buf, nullptr);
     if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
     // q, k, v; rotary; cache write; attention over the draft's own cache
@@ -409,16 +432,17 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     ra.Hq = dm.Hq; ra.Hkv = dm.Hkv; ra.d = dm.d; ra.q_out = b.q_buf; ra.paged = p.attn.paged;
     ra.kc = draft_kv->k; ra.vc = draft_kv->v; ra.page_table = draft_kv->page_table;
     ra.page_size = p.attn.page_size; ra.max_pages = p.attn.max_pages; ra.l_max = p.attn.l_max;
+    ra.n_pages = p.attn.n_pages; ra.status = status;
     if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
   } else {
-    if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, io.tok, io.hidden_in, b.act, s), "embed_concat"))) return rc;
+    if ((rc = check_hip(launch_embed_concat(dm, B, w->embed, io.tok, io.hidden_in, b.act, s, status), "embed_concat"))) return rc;
     if ((rc = run_gemm(p.fc, mf, bf16, w->w_fc, nullptr, nullptr, b, s, "gemm fc"))) return rc;
     if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.fc.ksplit, p.fc.planes, nullptr, w->ln_attn,
                                            b.x_buf, nullptr, b.act, s), "norm attn"))) return rc;
     if ((rc = run_gemm(p.qkv, mf, bf16, w->w_q, w->w_k, w->w_v, b, s, "gemm qkv"))) return rc;
     if ((rc = check_hip(launch_rope_kvwrite(dm, B, p.W, b.partial, p.qkv.ksplit, p.qkv.planes, io.pos, io.level, io.node,
                                             b.q_buf, p.attn.paged, draft_kv->k, draft_kv->v, draft_kv->page_table,
-                                            p.attn.page_size, p.attn.max_pages, p.attn.l_max, s), "rope"))) return rc;
+                                            p.attn.page_size, p.attn.max_pages, p.attn.l_max, s, p.attn.n_pages, status), "rope"))) return rc;
   }
   AttnArgs at = p.attn;
   at.q = b.q_buf;
@@ -428,13 +452,8 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
   at.n_blk = io.n_blk;
   at.scale = 1.0f / sqrtf(static_cast<float>(dm.d));
   at.out = b.attn_out;
-  {
-    Carver c(b.attn_ws);
-    const size_t R = static_cast<size_t>(at.Hq / at.Hkv) * at.n_q;
-    const size_t units = static_cast<size_t>(at.B) * at.Hkv * at.nsplit;
-    at.part_o = c.take<float>(units * R * at.d * sizeof(float));
-    at.part_ml = c.take<float>(units * R * 2 * sizeof(float));
-  }
+  at.status = status;
+  attn_carve(at, b.attn_ws);
   if ((rc = check_hip(launch_attn(at, s, &g_prof_hook, SPECEXIT_PROF_DRAFT_ATTN), "draft attention"))) return rc;
   if (p.gemv) {
     const int piece = 3 * num_cus();
@@ -559,6 +578,7 @@ int32_t specexit_copy_probe(const void* src, void* dst, size_t bytes, int32_t no
 
 int32_t specexit_profile_events(int32_t kernel, void* const* start_events, void* const* stop_events, int32_t n) {
   if (kernel < 0 || kernel > 3) return fail(SPECEXIT_EINVAL, "profile_events: unknown kernel id %d", kernel);
+  std::lock_guard<std::mutex> lock(g_prof_mu);
   ProfSlot& sl = g_prof[kernel];
   if (n < 0) return static_cast<int32_t>(sl.used);
   sl.start.clear();
@@ -571,7 +591,44 @@ int32_t specexit_profile_events(int32_t kernel, void* const* start_events, void*
   }
   return SPECEXIT_OK;
 }
-uint32_t specexit_version(void) { return 0x00010000u; }
+uint32_t specexit_version(void) { return 0x00020000u; }
+
+int32_t specexit_set_dev_status(int32_t* dev_status) {
+  g_dev_status = dev_status;
+  return SPECEXIT_OK;
+}
+
+size_t specexit_workspace_bytes(int32_t op, const void* desc, int32_t B, int32_t n_q) {
+  switch (op) {
+    case SPECEXIT_OP_DRAFT_STEP: {
+      const specexit_draft_query* q = static_cast<const specexit_draft_query*>(desc);
+      if (!q || q->struct_size != sizeof(*q)) return 0;
+      (void)n_q;
+      return specexit_draft_step_workspace_bytes(q->desc, q->draft_kv, B);
+    }
+    case SPECEXIT_OP_DRAFT_TREE_LEVEL: {
+      const specexit_draft_query* q = static_cast<const specexit_draft_query*>(desc);
+      if (!q || q->struct_size != sizeof(*q)) return 0;
+      return specexit_draft_tree_level_workspace_bytes(q->desc, q->draft_kv, B, n_q, q->top_b);
+    }
+    case SPECEXIT_OP_VERIFY_ATTN: {
+      const specexit_attn_query* q = static_cast<const specexit_attn_query*>(desc);
+      if (!q || q->struct_size != sizeof(*q)) return 0;
+      return specexit_verify_attn_workspace_bytes(q->kv, B, n_q, q->n_q_heads);
+    }
+    case SPECEXIT_OP_LMHEAD_ARGMAX: {
+      const specexit_lmhead_query* q = static_cast<const specexit_lmhead_query*>(desc);
+      if (!q || q->struct_size != sizeof(*q) || B < 1 || n_q < 1) return 0;
+      return specexit_lmhead_argmax_workspace_bytes(q->dtype, B * n_q, q->hidden, q->vocab, q->n_extra);
+    }
+    case SPECEXIT_OP_ACCEPT_EXIT:
+    case SPECEXIT_OP_KV_COMPACT:
+      return 0;   // these calls use no scratch memory
+    default:
+      fail(SPECEXIT_EINVAL, "workspace_bytes: unknown op %d", op);
+      return 0;
+  }
+}
 
 size_t specexit_draft_step_workspace_bytes(const specexit_model_desc* desc, const specexit_kv_view* draft_kv, int32_t B) {
   DraftPlan p;
@@ -615,6 +672,7 @@ int32_t specexit_draft_tree_level(const specexit_model_desc* desc, const specexi
   if (level < 0) return fail(SPECEXIT_EINVAL, "draft_tree_level: level < 0");
   if (n_blk < 1 || n_blk > SPECEXIT_MAX_NQ) return fail(SPECEXIT_EINVAL, "draft_tree_level: n_blk %d outside 1..64", n_blk);
   if (!node || !anc_mask) return fail(SPECEXIT_EINVAL, "draft_tree_level: node ids or ancestor masks missing");
+  if (n_blk > p.attn.l_max) return fail(SPECEXIT_EINVAL, "draft_tree_level: the cache holds fewer entries per sequence than the block's %d", n_blk);
   DraftIO io;
   memset(&io, 0, sizeof(io));
   io.tok = tok; io.hidden_in = hidden_in; io.pos = ctx_len; io.level = level; io.node = node;
@@ -632,7 +690,6 @@ size_t specexit_verify_attn_workspace_bytes(const specexit_kv_view* kv, int32_t 
 int32_t specexit_verify_attn(const specexit_kv_view* kv, int32_t B, int32_t n_q, int32_t n_q_heads, const void* q,
                              const int32_t* ctx_len, const uint64_t* mask, float scale, void* out,
                              void* workspace, size_t workspace_bytes, uint32_t flags, void* stream) {
-  (void)flags;
   AttnArgs a;
   int32_t rc = fill_attn(a, kv, B, n_q, n_q_heads, "verify_attn");
   if (rc) return rc;
@@ -646,11 +703,8 @@ int32_t specexit_verify_attn(const specexit_kv_view* kv, int32_t B, int32_t n_q,
   a.mask = mask;
   a.scale = scale;
   a.out = out;
-  Carver c(workspace);
-  const size_t R = static_cast<size_t>(a.Hq / a.Hkv) * a.n_q;
-  const size_t units = static_cast<size_t>(a.B) * a.Hkv * a.nsplit;
-  a.part_o = c.take<float>(units * R * a.d * sizeof(float));
-  a.part_ml = c.take<float>(units * R * 2 * sizeof(float));
+  a.status = status_for(flags);
+  attn_carve(a, workspace);
   return check_hip(launch_attn(a, static_cast<hipStream_t>(stream), &g_prof_hook, SPECEXIT_PROF_VERIFY_ATTN), "verify_attn");
 }
 
@@ -848,7 +902,6 @@ int32_t specexit_kv_compact(const specexit_kv_view* kv, int32_t n_layers, int64_
                             int32_t n_q, const int32_t* ctx_len, const int32_t* accept_path,
                             const int32_t* accept_len, const int32_t* last_node, const void* block_hidden,
                             int32_t D, void* hidden_next, uint32_t flags, void* stream) {
-  (void)flags;
   int32_t rc = check_kv(kv, "kv_compact");
   if (rc) return rc;
   if (B < 1) return fail(SPECEXIT_EINVAL, "kv_compact: B < 1");
@@ -864,6 +917,8 @@ int32_t specexit_kv_compact(const specexit_kv_view* kv, int32_t n_layers, int64_
   a.page_size = a.paged ? kv->page_size : 16;
   a.max_pages = kv->max_pages_per_seq;
   a.l_max = a.paged ? static_cast<int64_t>(kv->max_pages_per_seq) * kv->page_size : kv->l_max;
+  a.n_pages = a.paged ? kv->n_pages : 0;
+  a.status = status_for(flags);
   a.layer_stride_bytes = n_layers > 1 ? layer_stride_bytes : 0;
   a.n_layers = n_layers; a.B = B; a.n_q = n_q; a.Hkv = kv->n_kv_heads;
   a.row_bytes = static_cast<int>(kv->head_dim * esize(kv->dtype));

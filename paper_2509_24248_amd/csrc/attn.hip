@@ -1,9 +1,10 @@
-// Verification attention (Alg. 1, "forward through M_t with tree attention"): the draft
+// Verification attention (Alg. 1, the target's verification forward over the draft block): the
 // block's n_q queries of every head attend to the whole cached context plus the block
 // entries their ancestor mask allows.  The KV cache is read once: all G * n_q query rows
-// that share a KV head are processed together, the cache length is cut into chunks that
-// run as independent workgroups (each keeps an online softmax), and a second kernel
-// merges the chunks' (max, sum, output) triples exactly.
+// that share a KV head are processed together, the keys of all sequences are dealt to the
+// workgroups in equal shares (attn_sched.hpp; each segment keeps an online softmax), and a
+// second kernel merges the segments' (max, sum, output) triples exactly.
+#include "attn_sched.hpp"
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -17,7 +18,7 @@ template <typename T>
 __device__ __forceinline__ const T* kv_row(const AttnArgs& a, const void* pool, int b, int g, int64_t p) {
   const T* base = static_cast<const T*>(pool);
   if (a.paged) {
-    const int page = a.page_table[static_cast<size_t>(b) * a.max_pages + p / a.page_size];
+    const int page = checked_page(a.page_table[static_cast<size_t>(b) * a.max_pages + p / a.page_size], a.n_pages, a.status);
     return base + ((static_cast<size_t>(page) * a.Hkv + g) * a.page_size + p % a.page_size) * a.d;
   }
   return base + ((static_cast<size_t>(b) * a.Hkv + g) * a.l_max + p) * a.d;
@@ -27,14 +28,9 @@ __device__ __forceinline__ const T* kv_row(const AttnArgs& a, const void* pool, 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
   extern __shared__ float smem[];
-  const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   const int G = a.Hq / a.Hkv;
   const int R = G * a.n_q;
-  const int L = a.ctx_len[b];
-  const int total = L + a.n_blk;
-  const int s0 = split * a.chunk;
-  if (s0 >= total) return;
-  const int s1 = min(total, s0 + a.chunk);
+  const int tid = threadIdx.x;
   constexpr int DP = D + 4;
   float* Qs = smem;                 // [R][D]
   float* Ks = Qs + R * D;           // [kTK][DP]
@@ -43,7 +39,20 @@ __global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
   float* Ms = Ss + R * kTK;         // [R] running max
   float* Ls = Ms + R;               // [R] running sum
   float* As = Ls + R;               // [R] rescale of this tile
-  const int tid = threadIdx.x;
+  int* sched_lds = reinterpret_cast<int*>(As + R);   // [B + 1]
+  attn_sched_build(a, sched_lds);
+  const int Tg = a.Hkv * sched_lds[a.B];     // granules on the line
+  const int W = attn_sched_workgroups(Tg, a.wgrid);
+  if (blockIdx.x == 0) {
+    for (int i = tid; i <= a.B; i += 256) a.sched[i] = sched_lds[i];
+    if (tid == 0) a.sched[a.B + 1] = W;
+  }
+  if (static_cast<int>(blockIdx.x) >= W) return;
+  const int x_hi = attn_sched_lo(blockIdx.x + 1, Tg, W);
+  for (int x_cur = attn_sched_lo(blockIdx.x, Tg, W); x_cur < x_hi;) {
+  const AttnSeg seg = attn_sched_segment(a, sched_lds, x_cur, x_hi);
+  x_cur = seg.next;
+  const int g = seg.g, b = seg.b, L = seg.L, s0 = seg.s0, s1 = seg.s1;
 
   for (int idx = tid; idx < R * D; idx += 256) {
     const int r = idx / D, c = idx % D;
@@ -155,7 +164,7 @@ __global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
     }
     __syncthreads();
   }
-  const size_t unit = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit + split;
+  const size_t unit = static_cast<size_t>(blockIdx.x) + static_cast<size_t>(b) * a.Hkv + g;   // partial slot of segment (w, u)
 #pragma unroll
   for (int u = 0; u < MAXU; ++u) {
     const int r = r0 + u * RSTEP;
@@ -165,9 +174,11 @@ __global__ __launch_bounds__(256) void k_attn_split_valu(const AttnArgs a) {
     a.part_ml[(unit * R + r) * 2 + 0] = Ms[r];
     a.part_ml[(unit * R + r) * 2 + 1] = Ls[r];
   }
+  __syncthreads();   // a further segment restarts the running maxima and sums
+  }
 }
 
-// Merge the chunks of one (sequence, query, head): exact log-sum-exp combination.  One
+// Merge the segments of one (sequence, query, head): exact log-sum-exp combination.  One
 // workgroup per output row: the chunks' weights exp(m_s - max) are formed once in LDS, then
 // the threads split into groups that each take every NG-th chunk of one float4 column, so
 // all partial outputs are requested at once; the groups are added in a fixed order.
@@ -177,17 +188,21 @@ template <typename T, int D>
 __global__ __launch_bounds__(kCombThreads) void k_attn_combine(const AttnArgs a) {
   constexpr int C4 = D / 4;                 // float4 columns of a row
   constexpr int NG = kCombThreads / C4;     // chunk groups
-  extern __shared__ float w_lds[];          // [nsplit] weights, then NG x C4 float4 for the group sums
+  extern __shared__ float w_lds[];          // [wgrid] weights (a unit has at most that many segments), then NG x C4 float4 for the group sums
   __shared__ float red[kCombThreads / 64];
   const int h = blockIdx.x, i = blockIdx.y, b = blockIdx.z;
   const int G = a.Hq / a.Hkv;
   const int R = G * a.n_q;
   const int g = h / G, r = i * G + h % G;
-  const int total = a.ctx_len[b] + a.n_blk;
-  const int nact = min((total + a.chunk - 1) / a.chunk, a.nsplit);
-  const size_t unit0 = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit;
-  const float* ml = a.part_ml + (unit0 * R + r) * 2;          // chunk s at ml[s * R * 2]
-  const float* po = a.part_o + (unit0 * R + r) * D;            // chunk s at po[s * R * D]
+  // the segments of this row's unit: consecutive slots, one per workgroup whose range touched it
+  const int n_b = a.sched[b + 1] - a.sched[b];
+  const int Tg = a.Hkv * a.sched[a.B], W = a.sched[a.B + 1];
+  const int p_u = a.Hkv * a.sched[b] + g * n_b;
+  const int w_first = attn_sched_owner(p_u, Tg, W);
+  const int nact = attn_sched_owner(p_u + n_b - 1, Tg, W) - w_first + 1;
+  const size_t unit0 = static_cast<size_t>(w_first) + static_cast<size_t>(b) * a.Hkv + g;
+  const float* ml = a.part_ml + (unit0 * R + r) * 2;          // segment s at ml[s * R * 2]
+  const float* po = a.part_o + (unit0 * R + r) * D;            // segment s at po[s * R * D]
   float mloc = -INFINITY;
   for (int s = threadIdx.x; s < nact; s += kCombThreads) mloc = fmaxf(mloc, ml[static_cast<size_t>(s) * R * 2]);
   mloc = wave_max(mloc);
@@ -229,7 +244,7 @@ __global__ __launch_bounds__(kCombThreads) void k_attn_combine(const AttnArgs a)
         acc.z = fmaf(w[u], o[u].z, acc.z); acc.w = fmaf(w[u], o[u].w, acc.w);
       }
   }
-  float4* gs = reinterpret_cast<float4*>(w_lds + ((a.nsplit + 3) & ~3));
+  float4* gs = reinterpret_cast<float4*>(w_lds + ((a.wgrid + 3) & ~3));
   gs[sg * C4 + c4] = acc;
   __syncthreads();
   if (sg == 0) {
@@ -246,57 +261,75 @@ __global__ __launch_bounds__(kCombThreads) void k_attn_combine(const AttnArgs a)
 
 size_t valu_smem_bytes(const AttnArgs& a) {
   const int R = (a.Hq / a.Hkv) * a.n_q;
-  return sizeof(float) * (static_cast<size_t>(R) * a.d + 2 * kTK * (a.d + 4) + static_cast<size_t>(R) * kTK + 3 * R);
+  return sizeof(float) * (static_cast<size_t>(R) * a.d + 2 * kTK * (a.d + 4) + static_cast<size_t>(R) * kTK + 3 * R + a.B + 1);
 }
 
 template <typename T, int D>
 hipError_t launch_valu(const AttnArgs& a, hipStream_t s) {
   const size_t smem = valu_smem_bytes(a);
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_split_valu<T, D>),
+  // set once per process; a function-local static is initialised under the language's own lock,
+  // so first calls from several host threads are safe
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_split_valu<T, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  hipLaunchKernelGGL((k_attn_split_valu<T, D>), dim3(a.nsplit, a.Hkv, a.B), dim3(256), smem, s, a);
+  if (attr != hipSuccess) return attr;
+  hipLaunchKernelGGL((k_attn_split_valu<T, D>), dim3(a.wgrid), dim3(256), smem, s, a);
   return hipGetLastError();
 }
 
 }  // namespace
 
-void attn_plan(AttnArgs& a, int num_cus) {
-  // Chunk of the cache length handled by one workgroup.  The host knows only the upper
-  // bound l_max of the lengths, so the grid is sized for it and workgroups past a sequence's
-  // end leave at once.  Small problems get one workgroup per CU at most (a second round of
-  // workgroups would double their latency); large ones get about three rounds so that
-  // sequences of different length balance out.
+constexpr size_t kCombineLdsMax = 60 * 1024;
+
+size_t combine_lds_bytes(int wgrid) { return (static_cast<size_t>((wgrid + 3) & ~3) + kCombThreads * 4) * sizeof(float); }
+
+bool attn_plan(AttnArgs& a, int num_cus) {
+  // The host knows only the upper bound l_max of the lengths; the kernels deal the keys that
+  // are really there to the workgroups in equal shares.  Here only the number of workgroups is
+  // set: as many as are resident at once (two of the matrix-core kernel fit a compute unit),
+  // fewer when even the longest possible caches would leave them less than two granules (128
+  // keys) each, more when a share could otherwise exceed what one segment can hold.
   a.use_mfma = attn_mfma_supported(a) ? 1 : 0;
+  if (a.B > kAttnMaxSeqs || a.l_max < a.n_blk) return false;
   const int64_t units = static_cast<int64_t>(a.B) * a.Hkv;
-  const int64_t lmax = a.l_max;
-  const int64_t keys = units * lmax;
-  const int64_t rounds = keys >= static_cast<int64_t>(num_cus) * 3 * 1024 ? 3 : 1;
-  const int64_t per_cu = a.use_mfma ? 2 : 1;   // workgroups of the matrix-core kernel that fit a CU
-  const int64_t target = rounds * num_cus * (rounds == 1 ? per_cu : 1);
-  int64_t chunk = (keys + target - 1) / target;
-  chunk = ((chunk + 127) / 128) * 128;
-  if (chunk < 128) chunk = 128;
-  // never more workgroups than the target: rounding the split count up must not spill over
-  while (units * ((lmax + chunk - 1) / chunk) > target && chunk < lmax) chunk += 128;
-  if (a.use_mfma && chunk > attn_mfma_max_chunk(a)) chunk = attn_mfma_max_chunk(a) / 128 * 128;
-  a.chunk = static_cast<int>(chunk);
-  a.nsplit = static_cast<int>((lmax + chunk - 1) / chunk);
-  if (a.nsplit < 1) a.nsplit = 1;
+  const int64_t gmax = (a.l_max + kAttnGran - 1) / kAttnGran;      // granules of the longest possible unit
+  const int64_t tmax = units * gmax;
+  if (tmax >= (1ll << 30)) return false;
+  const int64_t resident = static_cast<int64_t>(num_cus) * (a.use_mfma ? 2 : 1);
+  int64_t w = tmax / 2 < resident ? tmax / 2 : resident;
+  if (w < 1) w = 1;
+  if (a.use_mfma) {
+    const int64_t seg_gran = attn_mfma_max_chunk(a) / kAttnGran;   // granules one segment may span
+    const int64_t need = (tmax + seg_gran - 1) / seg_gran;
+    if (w < need) w = need;
+  }
+  if (combine_lds_bytes(static_cast<int>(w)) > kCombineLdsMax) return false;
+  a.wgrid = static_cast<int>(w);
+  return true;
 }
+
+int attn_slots(const AttnArgs& a) { return a.wgrid + a.B * a.Hkv; }
 
 size_t attn_workspace_bytes(const AttnArgs& a) {
   const size_t R = static_cast<size_t>(a.Hq / a.Hkv) * a.n_q;
-  const size_t units = static_cast<size_t>(a.B) * a.Hkv * a.nsplit;
-  size_t o = units * R * a.d * sizeof(float);
+  const size_t slots = static_cast<size_t>(attn_slots(a));
+  size_t o = slots * R * a.d * sizeof(float);
   o = (o + 255) & ~static_cast<size_t>(255);
-  size_t ml = units * R * 2 * sizeof(float);
+  size_t ml = slots * R * 2 * sizeof(float);
   ml = (ml + 255) & ~static_cast<size_t>(255);
-  return o + ml;
+  size_t sc = static_cast<size_t>(a.B + 2) * sizeof(int);
+  sc = (sc + 255) & ~static_cast<size_t>(255);
+  return o + ml + sc;
+}
+
+void attn_carve(AttnArgs& a, void* workspace) {
+  const size_t R = static_cast<size_t>(a.Hq / a.Hkv) * a.n_q;
+  const size_t slots = static_cast<size_t>(attn_slots(a));
+  char* p = static_cast<char*>(workspace);
+  a.part_o = reinterpret_cast<float*>(p);
+  p += (slots * R * a.d * sizeof(float) + 255) & ~static_cast<size_t>(255);
+  a.part_ml = reinterpret_cast<float*>(p);
+  p += (slots * R * 2 * sizeof(float) + 255) & ~static_cast<size_t>(255);
+  a.sched = reinterpret_cast<int*>(p);
 }
 
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s, KernelHook hook, int hook_id) {
@@ -312,8 +345,7 @@ hipError_t launch_attn(const AttnArgs& a, hipStream_t s, KernelHook hook, int ho
   if (hook) hook(hook_id, 1, s);
   if (e != hipSuccess) return e;
   const dim3 grid(a.Hq, a.n_q, a.B);
-  const size_t lds = (static_cast<size_t>((a.nsplit + 3) & ~3) + kCombThreads * 4) * sizeof(float);
-  if (lds > 60 * 1024) return hipErrorInvalidValue;
+  const size_t lds = combine_lds_bytes(a.wgrid);   // attn_plan made sure it fits
   if (a.dtype == 1) {
     if (a.d == 128) hipLaunchKernelGGL((k_attn_combine<bf16_t, 128>), grid, dim3(kCombThreads), lds, s, a);
     else hipLaunchKernelGGL((k_attn_combine<bf16_t, 64>), grid, dim3(kCombThreads), lds, s, a);

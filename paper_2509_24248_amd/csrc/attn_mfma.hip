@@ -1,7 +1,8 @@
 // bf16 verification attention on the matrix cores (head_dim 128), HBM-bound by design.
 //
-// grid = (KV chunks, KV heads, sequences).  A workgroup owns one chunk of one (sequence, KV
-// head) and all R = G * n_q query rows that share that head, so the cache is read once.
+// A workgroup takes an equal share of all keys of the launch (attn_sched.hpp): one or more
+// segments, each a key range of one (sequence, KV head) unit, processed against all
+// R = G * n_q query rows that share that head, so the cache is read once.
 //
 // Inside a workgroup there are two independent tile rings (key groups); ring kg takes the
 // 32-key tiles kg, kg+2, ... of the chunk.  A ring is S slots of 16 KB in LDS (K tile + V
@@ -17,6 +18,7 @@
 //                 registers.
 // One workgroup barrier per tile step hands a landed tile to the waves and frees the slot
 // consumed one step earlier.  The two rings merge at the end in a fixed order.
+#include "attn_sched.hpp"
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -64,6 +66,9 @@ __device__ __forceinline__ void load_to_lds16(const void* src, const void* lds_b
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(l), "v"(src) : "memory");
 }
 
+// LDS words of the schedule's prefix table (B + 1 entries, rounded to 16 bytes)
+__host__ __device__ constexpr int sched_words(int B) { return (B + 1 + 3) & ~3; }
+
 constexpr int front_bytes(int rp, int stages) {
   return kNK * stages * kSlot > rp * kORow * 4 ? kNK * stages * kSlot : rp * kORow * 4;
 }
@@ -76,24 +81,35 @@ template <int NR, int RTW, int S, bool PAGED>
 __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   constexpr int RP = 16 * NR * RTW;             // query rows covered (padded)
   // LDS: [ring 0: S slots][ring 1: S slots] (later overlaid by the merge buffer [RP][kORow]),
-  // then the (max, sum) table for the merge, then the page ids of the chunk
+  // then the (max, sum) table for the merge, the schedule's prefix table, the page ids of the segment
   constexpr int kFront = front_bytes(RP, S);
   extern __shared__ uint4 smem4[];
   char* smem = reinterpret_cast<char*>(smem4);
   float* ml_lds = reinterpret_cast<float*>(smem + kFront);
-  int* pg_lds = reinterpret_cast<int*>(smem + kFront + kNK * RP * 2 * sizeof(float));
+  int* sched_lds = reinterpret_cast<int*>(smem + kFront + kNK * RP * 2 * sizeof(float));
+  int* pg_lds = sched_lds + sched_words(a.B);
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kg = wv / NR, rr = wv % NR;
-  const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
   const int G = a.Hq / a.Hkv;
   const int R = G * a.n_q;
-  const int L = a.ctx_len[b];
-  const int total = L + a.n_blk;
-  const int s0 = split * a.chunk;
-  if (s0 >= total) return;  // the whole workgroup leaves together
-  const int s1 = min(total, s0 + a.chunk);
-  const int ntl = (s1 - s0 + 31) >> 5;          // 32-key tiles in this chunk
+  attn_sched_build(a, sched_lds);
+  const int T = a.Hkv * sched_lds[a.B];
+  const int W = attn_sched_workgroups(T, a.wgrid);
+  if (blockIdx.x == 0) {
+    // the merging kernel reads the split back from here
+    for (int i = threadIdx.x; i <= a.B; i += 64 * kNK * NR) a.sched[i] = sched_lds[i];
+    if (threadIdx.x == 0) a.sched[a.B + 1] = W;
+  }
+  if (static_cast<int>(blockIdx.x) >= W) return;  // the whole workgroup leaves together
+  const int x_hi = attn_sched_lo(blockIdx.x + 1, T, W);
+  for (int x_cur = attn_sched_lo(blockIdx.x, T, W); x_cur < x_hi;) {
+  const AttnSeg seg = attn_sched_segment(a, sched_lds, x_cur, x_hi);
+  x_cur = seg.next;
+  const int g = seg.g, b = seg.b;
+  const int L = seg.L;
+  const int s0 = seg.s0, s1 = seg.s1;
+  const int ntl = (s1 - s0 + 31) >> 5;          // 32-key tiles in this segment
   const int nit = (ntl + kNK - 1) / kNK;        // tile steps (the same for both rings)
   const int fr = lane & 15, fq = lane >> 4;
   char* ring = smem + kg * (S * kSlot);
@@ -115,14 +131,16 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
     rowmask[t] = !valid ? 0ull : (a.mask ? a.mask[static_cast<size_t>(b) * a.mask_stride + i] : ((2ull << i) - 1ull));
   }
 
-  // ---- page ids of the chunk, copied to LDS once: loads from there do not count against
+  // ---- page ids of the segment, copied to LDS once: loads from there do not count against
   // the vector-memory counter that paces the tile loads
   const int ps_shift = 31 - __builtin_clz(a.page_size);
-  const int pg0 = s0 >> ps_shift;               // first page index of the chunk
+  const int pg0 = s0 >> ps_shift;               // first page index of the segment
   if (PAGED) {
     const int npg = ((s1 - 1) >> ps_shift) - pg0 + 1;
     const int32_t* ptab = a.page_table + static_cast<size_t>(b) * a.max_pages + pg0;
-    for (int i = threadIdx.x; i < npg; i += 64 * kNK * NR) pg_lds[i] = ptab[i];
+    for (int i = threadIdx.x; i < npg; i += 64 * kNK * NR) {
+      pg_lds[i] = checked_page(ptab[i], a.n_pages, a.status);   // never leave the pool
+    }
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));    // from here on vmcnt counts tile loads only
   __syncthreads();
@@ -327,7 +345,7 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
     }
   }
   __syncthreads();   // also: every wave is done with the rings
-  const size_t unit = (static_cast<size_t>(b) * a.Hkv + g) * a.nsplit + split;
+  const size_t unit = static_cast<size_t>(blockIdx.x) + static_cast<size_t>(b) * a.Hkv + g;   // partial slot of segment (w, u)
   float fself[RTW];
 #pragma unroll
   for (int t = 0; t < RTW; ++t) {
@@ -371,6 +389,9 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
     *reinterpret_cast<float4*>(a.part_o + (unit * R + r) * 128 + c4 * 4) =
         *reinterpret_cast<const float4*>(o_lds + r * kORow + c4 * 4);
   }
+  // a further segment refills the rings under the merge buffer: its first loads are issued after
+  // the barrier that follows the page-id copy, which every thread reaches after these reads
+  }
 }
 
 constexpr int kStages = 2;
@@ -378,16 +399,14 @@ constexpr int kStages = 2;
 template <int NR, int RTW, bool PAGED>
 hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   static_assert(NR * RTW <= 8, "at most 128 query rows");
-  static bool attr_set = false;
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_ring<NR, RTW, kStages, PAGED>),
+  // set once per process; a function-local static is initialised under the language's own lock,
+  // so first calls from several host threads are safe
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_ring<NR, RTW, kStages, PAGED>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (attr != hipSuccess) return attr;
   const size_t smem = static_cast<size_t>(front_bytes(16 * NR * RTW, kStages)) + static_cast<size_t>(kNK) * NR * RTW * 16 * 2 * sizeof(float) +
-                      (PAGED ? static_cast<size_t>(kMaxChunkPages + 1) * sizeof(int) : 0);
-  hipLaunchKernelGGL((k_attn_ring<NR, RTW, kStages, PAGED>), dim3(a.nsplit, a.Hkv, a.B), dim3(64 * kNK * NR), smem, s, a);
+                      static_cast<size_t>(sched_words(a.B)) * sizeof(int) + (PAGED ? static_cast<size_t>(kMaxChunkPages + 1) * sizeof(int) : 0);
+  hipLaunchKernelGGL((k_attn_ring<NR, RTW, kStages, PAGED>), dim3(a.wgrid), dim3(64 * kNK * NR), smem, s, a);
   return hipGetLastError();
 }
 
@@ -408,7 +427,6 @@ int attn_mfma_max_chunk(const AttnArgs& a) { return a.paged ? kMaxChunkPages * a
 
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s) {
   const int R = (a.Hq / a.Hkv) * a.n_q;
-  if (a.paged && a.chunk > kMaxChunkPages * a.page_size) return hipErrorInvalidValue;
   switch ((R + 15) / 16) {
     case 1: return launch_nr<1, 1>(a, s);
     case 2: return launch_nr<2, 1>(a, s);

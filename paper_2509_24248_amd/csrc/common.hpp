@@ -99,4 +99,35 @@ __device__ __forceinline__ void load_agent16x4(const float* p0, const float* p1,
 
 __device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
 
+// Values read from device arrays never reach an address unchecked: they are forced into range
+// (a bad value then gives a wrong result for its row, never a fault), and the first one seen is
+// reported in the caller's device status word when one was given.
+constexpr int kStatusBadLength = 1;  // ctx_len / pos < 0 or beyond the cache capacity
+constexpr int kStatusBadPage = 2;    // page id outside 0 .. n_pages-1
+constexpr int kStatusBadToken = 3;   // token id outside 0 .. V-1
+constexpr int kStatusBadNode = 4;    // node id, path entry or row index outside its block
+
+__device__ __forceinline__ void report_status(int* status, int code) {
+  if (status) atomicCAS(status, 0, code);
+}
+
+__device__ __forceinline__ int checked_page(int page, int64_t n_pages, int* status) {
+  if (static_cast<uint32_t>(page) < static_cast<uint32_t>(n_pages)) return page;
+  report_status(status, kStatusBadPage);
+  return 0;
+}
+
+// for writes: a cache entry whose page id is out of range is not written at all
+__device__ __forceinline__ bool page_in_pool(int page, int64_t n_pages, int* status) {
+  if (static_cast<uint32_t>(page) < static_cast<uint32_t>(n_pages)) return true;
+  report_status(status, kStatusBadPage);
+  return false;
+}
+
+__device__ __forceinline__ int checked_token(int tok, int vocab, int* status) {
+  if (static_cast<uint32_t>(tok) < static_cast<uint32_t>(vocab)) return tok;
+  report_status(status, kStatusBadToken);
+  return 0;
+}
+
 }  // namespace sx

@@ -27,12 +27,12 @@ __device__ __forceinline__ void gather_partial(const float* partial, int nslices
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void k_embed_concat(int D, const T* __restrict__ embed,
+__global__ __launch_bounds__(256) void k_embed_concat(int D, int V, int* status, const T* __restrict__ embed,
                                                       const int32_t* __restrict__ tok,
                                                       const T* __restrict__ hidden_in,
                                                       float* __restrict__ act) {
   const int b = blockIdx.x;
-  const T* e = embed + static_cast<size_t>(tok[b]) * D;
+  const T* e = embed + static_cast<size_t>(checked_token(tok[b], V, status)) * D;
   const T* h = hidden_in + static_cast<size_t>(b) * D;
   for (int g8 = threadIdx.x; g8 < 2 * D / 8; g8 += 256) {
     const int k = g8 * 8;
@@ -124,7 +124,7 @@ __global__ void k_rope_kvwrite(int M, int W, int Hq, int Hkv, int d, const float
                                const int32_t* __restrict__ node, float theta,
                                T* __restrict__ q_out, int paged, T* __restrict__ kc, T* __restrict__ vc,
                                const int32_t* __restrict__ page_table, int page_size, int max_pages,
-                               int64_t l_max) {
+                               int64_t l_max, int64_t n_pages, int* status) {
   const int r = blockIdx.x, hh = blockIdx.y, c = threadIdx.x;  // c in [0, d/2)
   const int b = r / W;
   const int N = (Hq + 2 * Hkv) * d;
@@ -162,6 +162,7 @@ __global__ void k_rope_kvwrite(int M, int W, int Hq, int Hkv, int d, const float
   size_t off;
   if (paged) {
     const int page = page_table[static_cast<size_t>(b) * max_pages + slot / page_size];
+    if (!page_in_pool(page, n_pages, status)) return;
     off = ((static_cast<size_t>(page) * Hkv + h) * page_size + slot % page_size) * d;
   } else {
     off = ((static_cast<size_t>(b) * Hkv + h) * l_max + slot) * d;
@@ -212,12 +213,12 @@ __global__ void k_head_finalize(int B, int rem_activation, const int32_t* __rest
 }  // namespace
 
 hipError_t launch_embed_concat(const DraftDims& dm, int B, const void* embed, const int32_t* tok,
-                               const void* hidden_in, float* act, hipStream_t s) {
+                               const void* hidden_in, float* act, hipStream_t s, int* status) {
   if (dm.dtype == 1)
-    hipLaunchKernelGGL(k_embed_concat<bf16_t>, dim3(B), dim3(256), 0, s, dm.D, static_cast<const bf16_t*>(embed),
+    hipLaunchKernelGGL(k_embed_concat<bf16_t>, dim3(B), dim3(256), 0, s, dm.D, dm.V, status, static_cast<const bf16_t*>(embed),
                        tok, static_cast<const bf16_t*>(hidden_in), act);
   else
-    hipLaunchKernelGGL(k_embed_concat<float>, dim3(B), dim3(256), 0, s, dm.D, static_cast<const float*>(embed),
+    hipLaunchKernelGGL(k_embed_concat<float>, dim3(B), dim3(256), 0, s, dm.D, dm.V, status, static_cast<const float*>(embed),
                        tok, static_cast<const float*>(hidden_in), act);
   return hipGetLastError();
 }
@@ -237,16 +238,16 @@ hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* pa
 hipError_t launch_rope_kvwrite(const DraftDims& dm, int M, int W, const float* partial, int nslices,
                                int planes, const int32_t* pos, int level, const int32_t* node, void* q_out,
                                int kv_paged, void* kc, void* vc, const int32_t* page_table, int page_size,
-                               int max_pages, int64_t l_max, hipStream_t s) {
+                               int max_pages, int64_t l_max, hipStream_t s, int64_t n_pages, int* status) {
   const dim3 grid(M, dm.Hq + 2 * dm.Hkv), block(dm.d / 2);
   if (dm.dtype == 1)
     hipLaunchKernelGGL(k_rope_kvwrite<bf16_t>, grid, block, 0, s, M, W, dm.Hq, dm.Hkv, dm.d, partial, nslices, planes,
                        pos, level, node, dm.rope_theta, static_cast<bf16_t*>(q_out), kv_paged,
-                       static_cast<bf16_t*>(kc), static_cast<bf16_t*>(vc), page_table, page_size, max_pages, l_max);
+                       static_cast<bf16_t*>(kc), static_cast<bf16_t*>(vc), page_table, page_size, max_pages, l_max, n_pages, status);
   else
     hipLaunchKernelGGL(k_rope_kvwrite<float>, grid, block, 0, s, M, W, dm.Hq, dm.Hkv, dm.d, partial, nslices, planes,
                        pos, level, node, dm.rope_theta, static_cast<float*>(q_out), kv_paged,
-                       static_cast<float*>(kc), static_cast<float*>(vc), page_table, page_size, max_pages, l_max);
+                       static_cast<float*>(kc), static_cast<float*>(vc), page_table, page_size, max_pages, l_max, n_pages, status);
   return hipGetLastError();
 }
 

@@ -169,7 +169,7 @@ __device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_ld
       hi = *reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.a_src) + static_cast<size_t>(m) * g.K + k);
     } else {
       const int half = g.K >> 1;
-      const bf16_t* src = k < half ? static_cast<const bf16_t*>(g.a_embed) + static_cast<size_t>(g.a_tok[m]) * half + k
+      const bf16_t* src = k < half ? static_cast<const bf16_t*>(g.a_embed) + static_cast<size_t>(checked_token(g.a_tok[m], g.a_vocab, g.status)) * half + k
                                    : static_cast<const bf16_t*>(g.a_src) + static_cast<size_t>(m) * half + (k - half);
       hi = *reinterpret_cast<const uint4*>(src);
     }
@@ -508,6 +508,7 @@ void k_gemm_mfma(const GemmArgs g) {
           size_t off;
           if (ra.paged) {
             const int page = ra.page_table[static_cast<size_t>(b) * ra.max_pages + slot / ra.page_size];
+            if (!page_in_pool(page, ra.n_pages, ra.status)) continue;
             off = ((static_cast<size_t>(page) * ra.Hkv + h) * ra.page_size + slot % ra.page_size) * ra.d;
           } else {
             off = ((static_cast<size_t>(b) * ra.Hkv + h) * ra.l_max + slot) * ra.d;
@@ -898,13 +899,11 @@ size_t gemm_mfma_lds_bytes(const GemmArgs& g) {
 
 template <int MT, int PLANES, bool HEAD>
 static hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
-  static bool attr_set = false;
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_mfma<MT, PLANES, HEAD>),
+  // set once per process; a function-local static is initialised under the language's own lock,
+  // so first calls from several host threads are safe
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_mfma<MT, PLANES, HEAD>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (attr != hipSuccess) return attr;
   constexpr int NW = HEAD ? kHeadWaves : kGemmWaves;
   const dim3 grid((gemm_ntiles(g.N) + NW - 1) / NW, g.ksplit);
   hipLaunchKernelGGL((k_gemm_mfma<MT, PLANES, HEAD>), grid, dim3(64 * NW), gemm_mfma_lds_bytes(g), s, g);

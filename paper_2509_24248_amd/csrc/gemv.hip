@@ -102,7 +102,7 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
       unpack16(*reinterpret_cast<const uint4*>(static_cast<const bf16_t*>(g.a_src) + static_cast<size_t>(m) * K + k), f);
     } else {
       const int half = K >> 1;
-      const bf16_t* src = k < half ? static_cast<const bf16_t*>(g.a_embed) + static_cast<size_t>(g.a_tok[m]) * half + k
+      const bf16_t* src = k < half ? static_cast<const bf16_t*>(g.a_embed) + static_cast<size_t>(checked_token(g.a_tok[m], g.a_vocab, g.status)) * half + k
                                    : static_cast<const bf16_t*>(g.a_src) + static_cast<size_t>(m) * half + (k - half);
       unpack16(*reinterpret_cast<const uint4*>(src), f);
     }
@@ -220,13 +220,15 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
           const bool is_k = hh < ra.Hq + ra.Hkv;
           const int h = is_k ? hh - ra.Hq : hh - ra.Hq - ra.Hkv;
           size_t off;
+          bool ok = true;
           if (ra.paged) {
             const int page = ra.page_table[static_cast<size_t>(b) * ra.max_pages + slot / ra.page_size];
+            ok = page_in_pool(page, ra.n_pages, ra.status);
             off = ((static_cast<size_t>(page) * ra.Hkv + h) * ra.page_size + slot % ra.page_size) * ra.d;
           } else {
             off = ((static_cast<size_t>(b) * ra.Hkv + h) * ra.l_max + slot) * ra.d;
           }
-          dst = static_cast<bf16_t*>(is_k ? ra.kc : ra.vc) + off;
+          if (ok) dst = static_cast<bf16_t*>(is_k ? ra.kc : ra.vc) + off;
         }
         if (dst) {
           dst[c] = f32_to_bf16(x1);
@@ -272,13 +274,11 @@ __global__ __launch_bounds__(512) void k_gemv(const GemvArgs g) {
 template <int MR, int SIF, bool STREAM>
 hipError_t launch_mr_sif(const GemvArgs& g, hipStream_t s) {
   const size_t lds = gemv_lds_bytes(g);
-  static bool attr_set = false;
-  if (!attr_set) {
-    const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemv<MR, SIF, STREAM>),
+  // set once per process; a function-local static is initialised under the language's own lock,
+  // so first calls from several host threads are safe
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemv<MR, SIF, STREAM>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 512);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
+  if (attr != hipSuccess) return attr;
   hipLaunchKernelGGL((k_gemv<MR, SIF, STREAM>), dim3(g.grid), dim3(64 * g.waves), lds, s, g);
   return hipGetLastError();
 }

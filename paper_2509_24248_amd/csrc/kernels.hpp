@@ -28,6 +28,8 @@ struct RopeArgs {
   const int32_t* page_table;
   int page_size, max_pages;
   int64_t l_max;
+  int64_t n_pages;           // paged: pages in the pool (page ids are forced into it)
+  int* status;               // device error word or nullptr
 };
 
 // MFMA GEMM, activation pieces in LDS: one row of 16-byte entries per 8-wide k piece, one entry per
@@ -67,7 +69,9 @@ struct GemmArgs {
   int a_nslices;       // mode 4: ksplit * planes of the producing GEMM
   int a_src_planes;    //         and its planes
   const void* a_embed; // mode 2: embedding table [V][K/2]
-  const int32_t* a_tok;  // mode 2: token ids [M]
+  const int32_t* a_tok;  // mode 2: token ids [M], forced into 0 .. a_vocab-1
+  int a_vocab;
+  int* status;         // device error word or nullptr (first out-of-range token id seen)
   int kc;              // K elements of activations staged in LDS at a time (multiple of 128)
   int a_double;        // set by choose_ksplit: head, one plane, more than 64 rows (a_mode must be 1): two one-block buffers refilled in turn
   float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
@@ -99,7 +103,9 @@ struct GemvArgs {
   int a_mode;            // as GemmArgs: 0 fp32 rows, 1 bf16 rows, 2 [embed[tok] ; hidden], 3 RMSNorm of fp32 rows
   const void* a_src;
   const void* a_embed;
-  const int32_t* a_tok;
+  const int32_t* a_tok;  // mode 2: token ids [M], forced into 0 .. a_vocab-1
+  int a_vocab;
+  int* status;           // device error word or nullptr
   const float* a_ssq;
   int a_nssq;
   const void* a_gain;
@@ -171,17 +177,23 @@ struct AttnArgs {
   int mask_stride;           // mask words between two sequences' rows (n_q; 0 = all sequences share)
   float scale;
   void* out;                 // [B, n_q, Hq, d] in dtype
-  int chunk;                 // keys per split
-  int nsplit;                // grid extent over splits
-  float* part_o;             // [B][Hkv][nsplit][R][d]
-  float* part_ml;            // [B][Hkv][nsplit][R][2]  (running max, sum)
+  int wgrid;                 // workgroups of the split kernel; the keys of all (sequence, KV head) units
+                             // are dealt to them in equal shares on the device (attn_sched.hpp)
+  float* part_o;             // [wgrid + B*Hkv slots][R][d]
+  float* part_ml;            // [wgrid + B*Hkv slots][R][2]  (running max, sum)
+  int* sched;                // [B + 2] written by the split kernel for the merging kernel: prefix sums of the
+                             // sequences' granule counts, then the number of workgroups that took part
+  int64_t n_pages;           // paged: pages in the pool (page ids are forced into it)
+  int* status;               // device error word or nullptr: first out-of-range length / page id seen
   int use_mfma;              // matrix-core kernel (bf16, head_dim 128); its maxima are in log2 units
 };
 bool attn_mfma_supported(const AttnArgs& a);
 int attn_mfma_max_chunk(const AttnArgs& a);   // longest chunk the matrix-core kernel takes
+int attn_slots(const AttnArgs& a);            // partial-result slots a launch can write
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
-void attn_plan(AttnArgs& a, int num_cus);
+bool attn_plan(AttnArgs& a, int num_cus);      // false: the problem is outside what one launch can split
 size_t attn_workspace_bytes(const AttnArgs& a);
+void attn_carve(AttnArgs& a, void* workspace);   // points part_o / part_ml / sched into a workspace of that size
 // hook(id, 0 / 1, stream) is called right before / after the split-KV kernel's launch
 typedef void (*KernelHook)(int id, int phase, hipStream_t s);
 hipError_t launch_attn(const AttnArgs& a, hipStream_t s, KernelHook hook = nullptr, int hook_id = 0);
@@ -193,7 +205,7 @@ struct DraftDims {
   int rem_activation;
 };
 hipError_t launch_embed_concat(const DraftDims& dm, int B, const void* embed, const int32_t* tok,
-                               const void* hidden_in, float* act, hipStream_t s);
+                               const void* hidden_in, float* act, hipStream_t s, int* status = nullptr);
 // v[b][:] = residual[b][:] + sum of partial slices; optional copy to `sum_out` (fp32) and
 // `hidden_out` (storage type); then RMSNorm with gain -> act (fp32)
 hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* partial, int nslices,
@@ -203,7 +215,8 @@ hipError_t launch_reduce_norm(const DraftDims& dm, int B, int N, const float* pa
 hipError_t launch_rope_kvwrite(const DraftDims& dm, int M, int W, const float* partial, int nslices,
                                int planes, const int32_t* pos, int level, const int32_t* node, void* q_out,
                                int kv_paged, void* kc, void* vc, const int32_t* page_table, int page_size,
-                               int max_pages, int64_t l_max, hipStream_t s);
+                               int max_pages, int64_t l_max, hipStream_t s, int64_t n_pages = 0x7fffffff,
+                               int* status = nullptr);
 hipError_t launch_silu_mul(const DraftDims& dm, int B, const float* partial, int nslices, int planes,
                            float* act, hipStream_t s);
 hipError_t launch_head_finalize(const DraftDims& dm, int B, const int32_t* argmax_in,
@@ -220,10 +233,12 @@ struct CompactArgs {
   const int32_t* page_table;
   int page_size, max_pages;
   int64_t l_max;
+  int64_t n_pages;           // paged: pages in the pool (page ids are forced into it)
   int64_t layer_stride_bytes;
   int n_layers, B, n_q, Hkv;
   int row_bytes;             // head_dim * element size
   const int32_t *ctx_len, *accept_path, *accept_len, *last_node;
+  int* status;               // device error word or nullptr
   const void* block_hidden;  // [B][n_q][hidden_row_bytes] or nullptr
   void* hidden_next;         // [B][hidden_row_bytes]
   int hidden_row_bytes;

@@ -1,5 +1,5 @@
-// What a round leaves behind for the next one (Alg. 1, "update KV-cache and hidden states
-// accordingly"): the K/V entries of the accepted path, stored at cache positions
+// What a round leaves behind for the next one (Alg. 1, the cache-update step inside the exit
+// branch, applied after every round): the K/V entries of the accepted path, stored at cache positions
 // L + node during verification, move to L + 1 + j so that the cache again holds a plain
 // sequence; the target's hidden state of the last accepted node is handed on as the next
 // round's first draft input.  A few KB per (sequence, KV head, layer): latency-bound, so one
@@ -28,10 +28,12 @@ __global__ __launch_bounds__(kThreads) void k_kv_compact(const CompactArgs a) {
   const int32_t* path = a.accept_path + static_cast<size_t>(b) * a.n_q;
   const int lpr = a.row_bytes >> 4;                 // 16-byte pieces per row
   const bool in_cache = L >= 0 && static_cast<int64_t>(L) + a.n_q <= a.l_max;
+  if (!in_cache) report_status(a.status, kStatusBadLength);
 
   // ---- hidden state of the last accepted node -> next round's draft input
   if (h == 0 && layer == 0 && a.block_hidden) {
     int node = a.last_node[b];
+    if (node < 0 || node >= a.n_q) report_status(a.status, kStatusBadNode);
     node = max(0, min(node, a.n_q - 1));
     const uint4* src = reinterpret_cast<const uint4*>(static_cast<const char*>(a.block_hidden) +
                                                       (static_cast<size_t>(b) * a.n_q + node) * a.hidden_row_bytes);
@@ -50,6 +52,7 @@ __global__ __launch_bounds__(kThreads) void k_kv_compact(const CompactArgs a) {
     size_t row;
     if (a.paged) {
       const int pg = a.page_table[static_cast<size_t>(b) * a.max_pages + pos / a.page_size];
+      if (!page_in_pool(pg, a.n_pages, a.status)) return nullptr;   // a row of a page outside the pool is neither read nor written
       row = (static_cast<size_t>(pg) * a.Hkv + h) * a.page_size + pos % a.page_size;
     } else {
       row = (static_cast<size_t>(b) * a.Hkv + h) * a.l_max + pos;
@@ -67,8 +70,13 @@ __global__ __launch_bounds__(kThreads) void k_kv_compact(const CompactArgs a) {
       const int which = it / (rows * lpr), rem = it % (rows * lpr);
       const int j = first + rem / lpr, piece = rem % lpr;
       const int node = path[j];
-      if (node >= 1 && node < a.n_q)
-        buf[u] = reinterpret_cast<const uint4*>(row_ptr(which ? a.v : a.k, L + node))[piece];
+      buf[u] = make_uint4(0, 0, 0, 0);
+      if (node >= 1 && node < a.n_q) {
+        const char* src = row_ptr(which ? a.v : a.k, L + node);
+        if (src) buf[u] = reinterpret_cast<const uint4*>(src)[piece];
+      } else {
+        report_status(a.status, kStatusBadNode);
+      }
     }
   }
   __syncthreads();
@@ -79,8 +87,10 @@ __global__ __launch_bounds__(kThreads) void k_kv_compact(const CompactArgs a) {
       const int which = it / (rows * lpr), rem = it % (rows * lpr);
       const int j = first + rem / lpr, piece = rem % lpr;
       const int node = path[j];
-      if (node >= 1 && node < a.n_q)
-        reinterpret_cast<uint4*>(row_ptr(which ? a.v : a.k, L + 1 + j))[piece] = buf[u];
+      if (node >= 1 && node < a.n_q) {
+        char* dst = row_ptr(which ? a.v : a.k, L + 1 + j);
+        if (dst) reinterpret_cast<uint4*>(dst)[piece] = buf[u];
+      }
     }
   }
 }

@@ -1,6 +1,6 @@
 // Between two levels of tree drafting: the nodes of the next level take their tokens from
 // their parents' ranked continuations and their input hidden state from their parents'
-// output (the block that tree attention later verifies, Alg. 1, is filled in on the way).
+// output (the block that the target's verification forward later checks, Alg. 1, is filled in on the way).
 // A few KB per call: latency-bound, one launch per level.
 #include "common.hpp"
 #include "kernels.hpp"

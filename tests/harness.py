@@ -46,6 +46,34 @@ def workspace(nbytes):
     return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
 
 
+class Guarded:
+    """Output buffers with canary regions: every buffer handed to the library sits between two
+    512-byte pads filled with a byte pattern; check() fails if a kernel wrote outside its output."""
+    PAD, BYTE = 512, 0xA5
+
+    def __init__(self):
+        self.bufs = []
+
+    def empty(self, shape, dtype):
+        shape = tuple(int(x) for x in (shape if isinstance(shape, (tuple, list)) else (shape,)))
+        esz = torch.empty((), dtype=dtype).element_size()
+        nbytes = int(np.prod(shape)) * esz
+        body = (nbytes + 255) // 256 * 256
+        raw = torch.full((self.PAD + body + self.PAD,), self.BYTE, dtype=torch.uint8, device="cuda")
+        view = raw[self.PAD:self.PAD + nbytes].view(dtype).reshape(shape)
+        self.bufs.append((raw, nbytes))
+        return view
+
+    def empty_like(self, t):
+        return self.empty(tuple(t.shape), t.dtype)
+
+    def check(self):
+        torch.cuda.synchronize()
+        for raw, nbytes in self.bufs:
+            assert bool((raw[:self.PAD] == self.BYTE).all()), "a kernel wrote in front of its output buffer"
+            assert bool((raw[self.PAD + nbytes:] == self.BYTE).all()), "a kernel wrote behind its output buffer"
+
+
 # ----------------------------------------------------------------------------- attention
 
 def kv_view_of(shape, kv: gen.KVCache):
@@ -60,11 +88,12 @@ def gpu_verify_attn(shape, kv, q, ctx_len, mask, scale=None):
     view, keep = kv_view_of(shape, kv)
     B, n_q, Hq, d = q.shape
     qd = dev(q, shape)
-    out = torch.empty_like(qd)
+    guard = Guarded()
+    out = guard.empty_like(qd)
     ws = workspace(lib.specexit_verify_attn_workspace_bytes(view, B, n_q, Hq))
     lib.specexit_verify_attn(view, B, n_q, Hq, qd, dev(ctx_len.astype(np.int32)),
                              None if mask is None else dev(mask), d ** -0.5 if scale is None else scale, out, ws)
-    torch.cuda.synchronize()
+    guard.check()
     return host(out)
 
 
@@ -98,13 +127,14 @@ def gpu_lmhead(shape, hidden, w, n_extra=0, want_logits=True):
     V = w.shape[0] - n_extra
     dt = lib.BF16 if shape.dtype == "bf16" else lib.F32
     hd, wd = dev(hidden, shape), dev(w, shape)
-    am = torch.empty(M, dtype=torch.int32, device="cuda")
-    mx = torch.empty(M, dtype=torch.float32, device="cuda")
-    ex = torch.empty((M, max(n_extra, 1)), dtype=torch.float32, device="cuda")
-    lg = torch.empty((M, V), dtype=torch.float32, device="cuda") if want_logits else None
+    guard = Guarded()
+    am = guard.empty(M, torch.int32)
+    mx = guard.empty(M, torch.float32)
+    ex = guard.empty((M, max(n_extra, 1)), torch.float32)
+    lg = guard.empty((M, V), torch.float32) if want_logits else None
     ws = workspace(lib.specexit_lmhead_argmax_workspace_bytes(dt, M, D, V, n_extra))
     lib.specexit_lmhead_argmax(dt, M, D, V, n_extra, hd, wd, am, mx, ex if n_extra else None, lg, ws)
-    torch.cuda.synchronize()
+    guard.check()
     return host(am), host(mx), host(ex)[:, :n_extra], (host(lg) if want_logits else None)
 
 
@@ -128,13 +158,14 @@ class GpuDraft:
     def step(self, tok, hidden_in, pos, flags=0):
         shape, B = self.shape, self.shape.B
         hin = dev(hidden_in, shape)
-        hout = torch.empty_like(hin)
-        nt = torch.empty(B, dtype=torch.int32, device="cuda")
-        sr = torch.empty((B, 3), dtype=torch.float32, device="cuda")
-        sg = torch.empty((B, 3), dtype=torch.float32, device="cuda")
+        guard = Guarded()
+        hout = guard.empty_like(hin)
+        nt = guard.empty(B, torch.int32)
+        sr = guard.empty((B, 3), torch.float32)
+        sg = guard.empty((B, 3), torch.float32)
         self.lib.specexit_draft_step(self.desc, self.w, self.view, B, dev(tok.astype(np.int32)), hin,
                                      dev(pos.astype(np.int32)), hout, nt, sr, sg, self.ws, flags=flags)
-        torch.cuda.synchronize()
+        guard.check()
         return {"hidden_out": host(hout), "next_tok": host(nt), "sig_raw": host(sr), "sig": host(sg)}
 
     def cache(self):
@@ -169,7 +200,6 @@ class GpuDraft:
             cl = torch.empty((B, W, top_b), dtype=torch.float32, device="cuda")
             sr = torch.empty((B, W, 3), dtype=torch.float32, device="cuda")
             sg = torch.empty((B, W, 3), dtype=torch.float32, device="cuda")
-            print(f"  tree level {level}: rows {rows}", flush=True)
             lib.specexit_draft_tree_level(self.desc, self.w, self.view, B, W, tok, hid, ctx, level, i32(rows),
                                           dev(masks[rows]), max(rows) + 1, top_b, hout, ct, cl, sr, sg, ws)
             torch.cuda.synchronize()
@@ -241,11 +271,33 @@ def force_tree_gap(shape, w, kv, tok0, g0, L, parent, rank, top_b, gap=0.05, max
     raise AssertionError("could not force the logit gaps of the tree")
 
 
-def force_draft_gap(shape, w, kv, tok, g, pos, gap=0.05):
-    """Run the oracle once to get the final-normed hidden rows, then bump w_head's winners."""
-    kc, vc = kv.k.astype(np.float64), kv.v.astype(np.float64)
-    out = O.draft_step(oracle_dims(shape), w, kc, vc, tok, g, pos, kv.page_table if kv.paged else None,
-                       kv.page_size, store=lambda a: gen.store(shape, a.astype(np.float32)))
+def oracle_draft_rows(shape, w, kv, tok, g, pos, rows, kc=None, vc=None, progress=None):
+    """The oracle's draft forward for a sample of the step's rows (the rows of a step are independent:
+    row b reads and writes sequence b's cache only).  Returns {row: result of the oracle's row routine};
+    the cache arrays (kc, vc; default: kv's own, modified in place) receive the rows' new entries."""
+    kc = kv.k if kc is None else kc
+    vc = kv.v if vc is None else vc
+    out = {}
+    for b in rows:
+        if progress:
+            print(f"  oracle {progress}: row {b}", flush=True)
+        p = int(pos[b])
+        out[b] = O._draft_row(oracle_dims(shape), w, kc, vc, b, tok[b], g[b], p, p, np.arange(p + 1),
+                              kv.page_table if kv.paged else None, kv.page_size,
+                              lambda a: gen.store(shape, np.asarray(a, np.float32)))
+    return out
+
+
+def force_draft_gap(shape, w, kv, tok, g, pos, gap=0.05, rows=None):
+    """Run the oracle once to get the final-normed hidden rows, then bump w_head's winners
+    (rows: only these rows of the step are looked at)."""
+    if rows is not None:
+        res = oracle_draft_rows(shape, w, kv, tok, g, pos, rows, kv.k.copy(), kv.v.copy(), progress="gap forcing")
+        out = {"h_final": np.stack([res[b]["h_final"] for b in rows])}
+    else:
+        kc, vc = kv.k.astype(np.float64), kv.v.astype(np.float64)
+        out = O.draft_step(oracle_dims(shape), w, kc, vc, tok, g, pos, kv.page_table if kv.paged else None,
+                           kv.page_size, store=lambda a: gen.store(shape, a.astype(np.float32)))
     head = w["w_head"]
     V = shape.V
     new_tok_rows, _, _ = force_gap(out["h_final"].astype(np.float32), head[:V], V, gap, shape)
@@ -263,9 +315,10 @@ def gpu_accept_exit(cfg_kwargs, block_tok, parent, target_argmax, sig, ctx_len, 
     B, n_q = block_tok.shape
     cfg = lib.exit_cfg(**cfg_kwargs)
     i32 = lambda a: dev(np.asarray(a, dtype=np.int32))
-    outs = {k: torch.empty(B, dtype=torch.int32, device="cuda")
+    guard = Guarded()
+    outs = {k: guard.empty(B, torch.int32)
             for k in ("accept_len", "recover_tok", "last_node", "exit_flag", "new_ctx_len")}
-    outs["accept_path"] = torch.empty((B, n_q), dtype=torch.int32, device="cuda")
+    outs["accept_path"] = guard.empty((B, n_q), torch.int32)
     split = i32(split_tok) if len(split_tok) else None
     lib.specexit_accept_exit(cfg, B, n_q, i32(block_tok), None if parent is None else i32(parent),
                              i32(target_argmax), dev(np.asarray(sig, np.float32), dtype=torch.float32),
@@ -273,7 +326,7 @@ def gpu_accept_exit(cfg_kwargs, block_tok, parent, target_argmax, sig, ctx_len, 
                              state[3] if len(state) > 3 else None,
                              outs["accept_len"], outs["accept_path"], outs["recover_tok"], outs["last_node"],
                              outs["exit_flag"], outs["new_ctx_len"])
-    torch.cuda.synchronize()
+    guard.check()
     return {k: host(v) for k, v in outs.items()}
 
 

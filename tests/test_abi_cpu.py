@@ -54,3 +54,32 @@ def test_binding_matches_header_and_validates_on_the_host():
     assert sx.specexit_verify_attn_workspace_bytes(kv, 1, 7, 32) > 0
     assert sx.specexit_verify_attn_workspace_bytes(kv, 1, 65, 32) == 0
     assert sx.specexit_verify_attn_workspace_bytes(kv, 1, 7, 30) == 0
+
+
+@pytest.mark.skipif(not os.path.exists(LIB), reason="libspecexit.so not built")
+def test_generic_workspace_query_agrees_with_the_per_call_queries():
+    from paper_2509_24248_amd import binding as sx
+    kv = sx.KVView()
+    kv.struct_size = ctypes.sizeof(sx.KVView)
+    kv.layout, kv.dtype, kv.n_kv_heads, kv.head_dim, kv.k, kv.v, kv.l_max = 0, 1, 8, 128, 256, 256, 4200
+    desc = sx.model_desc(sx.BF16, 2560, 32, 8, 128, 9728, 151936)
+    for B in (1, 5):
+        a = sx.specexit_workspace_bytes(sx.OP_DRAFT_STEP, sx.draft_query(desc, kv), B, 1)
+        assert a == sx.specexit_draft_step_workspace_bytes(desc, kv, B) > 0
+        a = sx.specexit_workspace_bytes(sx.OP_DRAFT_TREE_LEVEL, sx.draft_query(desc, kv, top_b=3), B, 4)
+        assert a == sx.specexit_draft_tree_level_workspace_bytes(desc, kv, B, 4, 3) > 0
+        a = sx.specexit_workspace_bytes(sx.OP_VERIFY_ATTN, sx.attn_query(kv, 32), B, 7)
+        assert a == sx.specexit_verify_attn_workspace_bytes(kv, B, 7, 32) > 0
+        a = sx.specexit_workspace_bytes(sx.OP_LMHEAD_ARGMAX, sx.lmhead_query(sx.BF16, 2560, 151936), B, 7)
+        assert a == sx.specexit_lmhead_argmax_workspace_bytes(sx.BF16, B * 7, 2560, 151936, 0) > 0
+    assert sx.specexit_workspace_bytes(sx.OP_ACCEPT_EXIT, None, 4, 7) == 0
+    assert sx.specexit_workspace_bytes(sx.OP_KV_COMPACT, None, 4, 7) == 0
+    assert sx.specexit_workspace_bytes(99, None, 4, 7) == 0 and "unknown op" in sx.last_error()
+    assert sx.specexit_workspace_bytes(sx.OP_VERIFY_ATTN, None, 4, 7) == 0          # missing descriptor
+    q = sx.attn_query(kv, 32)
+    q.struct_size = 4
+    assert sx.specexit_workspace_bytes(sx.OP_VERIFY_ATTN, q, 4, 7) == 0             # another ABI size
+    # shapes one call cannot split are refused on the host
+    assert sx.specexit_verify_attn_workspace_bytes(kv, 2000, 7, 32) == 0 and "1024 sequences" in sx.last_error()
+    kv.l_max = 4
+    assert sx.specexit_verify_attn_workspace_bytes(kv, 1, 7, 32) == 0 and "fewer than the block" in sx.last_error()

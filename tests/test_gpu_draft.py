@@ -5,7 +5,7 @@ import pytest
 from oracle import specexit_oracle as O
 from workloads import gen
 
-from harness import TOL, GpuDraft, force_draft_gap, oracle_dims, rel_err
+from harness import TOL, GpuDraft, force_draft_gap, oracle_dims, oracle_draft_rows, rel_err
 
 pytestmark = pytest.mark.gpu
 
@@ -106,14 +106,52 @@ def test_full_size_config_1():
             np.testing.assert_array_equal(out[k], got[k], err_msg=f"prepared call {it}: {k}")
 
 
-@pytest.mark.timeout(900)
-def test_full_size_config_2_five_rows():
-    """Qwen3-8B-like sizes with more than four rows: the split-K matrix-core projections with their
-    reducing epilogues at full width (steps of up to four rows take the row-streaming path)."""
-    shape = gen.scaled(gen.config(2), B=5, ctx=(2048, 4096))
+def sampled_rows_step(shape, w, kv, tok, g, pos, rows, label):
+    """The step runs over all B rows on the GPU; the oracle computes the sampled rows (rows of a step are
+    independent of one another) and those are compared: token bit-exact, floats within tolerance."""
+    print(f"draft_step {label}: dtype={shape.dtype} B={shape.B} D={shape.D} I={shape.I} V={shape.V} "
+          f"pos={pos.tolist()} paged={kv.paged} oracle rows={rows}", flush=True)
+    gd = GpuDraft(shape, w, kv)                       # device copies are taken before the oracle writes its entries
+    got = gd.step(tok, g, pos)
+    gk, gv = gd.cache()
+    ref = oracle_draft_rows(shape, w, kv, tok, g, pos, rows, progress=label)
+    tol = TOL[shape.dtype]
+    for b in rows:
+        r = ref[b]
+        assert O.top2_gap(r["logits"][None, :])[0] > 0.05
+        assert got["next_tok"][b] == O.argmax_lowest(r["logits"]), f"row {b}"
+        assert rel_err(got["hidden_out"][b], r["hidden_out"]) < tol, f"row {b}"
+        assert rel_err(got["sig_raw"][b], r["sig_raw"]) < tol, f"row {b}"
+        assert rel_err(got["sig"][b], O.signal_activations(r["sig_raw"][None, :])[0]) < tol, f"row {b}"
+        p = int(pos[b])
+        if kv.paged:
+            pg, sl = kv.page_table[b, p // kv.page_size], p % kv.page_size
+            assert rel_err(gk[pg, :, sl], kv.k[pg, :, sl]) < tol and rel_err(gv[pg, :, sl], kv.v[pg, :, sl]) < tol
+        else:
+            assert rel_err(gk[b, :, p], kv.k[b, :, p]) < tol and rel_err(gv[b, :, p], kv.v[b, :, p]) < tol
+    assert np.isfinite(got["hidden_out"]).all() and (got["next_tok"] >= 0).all() and (got["next_tok"] < shape.V).all()
+
+
+@pytest.mark.timeout(1500)
+def test_full_size_config_2_all_eight_rows():
+    """Qwen3-8B-like sizes, B = 8, paged cache: the split-K matrix-core projections with their reducing
+    epilogues at full width (steps of up to four rows take the row-streaming path); every row compared."""
+    shape = gen.config(2)
     w, kv, tok, g, pos = setup(shape, 0, paged=True, norms=False)
-    w = force_draft_gap(shape, w, kv, tok, g, pos)
-    one_step(shape, w, kv, tok, g, pos, label="config 2 sizes, 5 rows")
+    rows = list(range(shape.B))
+    w = force_draft_gap(shape, w, kv, tok, g, pos, rows=rows)
+    sampled_rows_step(shape, w, kv, tok, g, pos, rows, "config 2 full size")
+
+
+@pytest.mark.timeout(1500)
+def test_full_size_config_4_sixteen_rows():
+    """32B-like sizes (D = 5120, I = 25600, 64 query heads, paged caches of 8k-32k entries), B = 16 rows in
+    the launch shapes bench.py times; the oracle checks the longest and the shortest sequence's rows and one more."""
+    shape = gen.config(4)
+    w, kv, tok, g, pos = setup(shape, 0, paged=True, norms=False)
+    rows = sorted({int(np.argmax(pos)), int(np.argmin(pos)), 7})
+    w = force_draft_gap(shape, w, kv, tok, g, pos, rows=rows)
+    sampled_rows_step(shape, w, kv, tok, g, pos, rows, "config 4 full size")
 
 
 def test_prepared_workspace_flag_gives_the_same_results_call_after_call():
