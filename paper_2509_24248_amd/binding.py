@@ -14,7 +14,7 @@ from typing import Optional
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libspecexit.so")
+LIB_PATH = os.environ.get("SPECEXIT_LIB") or os.path.join(HERE, "libspecexit.so")   # (a side-by-side build of the same sources)
 
 F32, BF16 = 0, 1
 KV_CONTIG, KV_PAGED = 0, 1

@@ -7,18 +7,19 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "libspecexit.so")
+# SPECEXIT_LIB names another output file and SPECEXIT_DEFS extra -D flags: side-by-side builds of kernel variants
+LIB = os.environ.get("SPECEXIT_LIB") or os.path.join(HERE, "libspecexit.so")
 SOURCES = ["api.hip", "gemm.hip", "gemv.hip", "attn.hip", "attn_mfma.hip", "draft.hip", "accept_exit.hip", "kv_compact.hip", "tree.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = (["-Rpass-analysis=kernel-resource-usage"] if os.environ.get("SPECEXIT_RESOURCE_REMARKS") else []) + ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          # packed fp32 VALU forms are kept out of the generated code on purpose
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + os.environ.get("SPECEXIT_DEFS", "").split()
 
 
 def build(verbose: bool = True) -> str:
     objs = []
     procs = []
-    bdir = os.path.join(HERE, "_build")
+    bdir = os.path.join(HERE, "_build") if not os.environ.get("SPECEXIT_LIB") else LIB + ".build"
     os.makedirs(bdir, exist_ok=True)
     for src in SOURCES:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))

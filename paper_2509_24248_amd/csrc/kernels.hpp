@@ -73,6 +73,7 @@ struct GemmArgs {
   int a_vocab;
   int* status;         // device error word or nullptr (first out-of-range token id seen)
   int kc;              // K elements of activations staged in LDS at a time (multiple of 128)
+  int nt;              // head mode: weight tiles per wave (1 or 2), set by choose_ksplit
   int a_double;        // set by choose_ksplit: head, one plane, more than 64 rows (a_mode must be 1): two one-block buffers refilled in turn
   float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
   // epi = 1: the workgroup that finishes a 128-row group last adds up the group's partial
@@ -138,7 +139,7 @@ hipError_t launch_zero_i32(int* p, int n, hipStream_t s);
 inline int gemm_mt(int M, int planes) { return (M * planes + 15) / 16; }
 
 bool gemm_mfma_supported(int M, int planes, int K);
-void choose_ksplit(GemmArgs& g, bool mfma);
+void choose_ksplit(GemmArgs& g, bool mfma, int num_cus);
 hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
 // reduce per-tile partial argmaxes: one result per activation row
