@@ -259,6 +259,24 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
 size_t specexit_lmhead_argmax_workspace_bytes(int32_t dtype, int32_t M, int32_t D, int32_t V,
                                               int32_t n_extra);
 
+/* ---- specexit_lmhead_argmax for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as
+ * specexit_lmhead_argmax, but no workspace: the scratch (the per-tile argmax candidates) lives in
+ * a buffer built into the library, SPECEXIT_NOALLOC_SCRATCH_BYTES per GPU, held from the first
+ * call on that GPU until the process ends.  The call allocates and frees nothing.  Shapes whose
+ * scratch would not fit (the query specexit_lmhead_argmax_workspace_bytes says how much) are
+ * refused with SPECEXIT_EWORKSPACE; 12 MiB covers every bf16 shape up to M = 144, V + n_extra =
+ * 151952.  All calls on one GPU share that GPU's buffer: calls that overlap in time on one GPU
+ * (two streams, two threads) race and must be ordered by the caller.  The buffer keeps the last
+ * call's contents; nothing in it has to be cleared between calls.  The first call on a GPU looks
+ * the buffer's address up and must therefore come before any stream capture. */
+#define SPECEXIT_NOALLOC_SCRATCH_BYTES (12u << 20)
+int32_t specexit_lmhead_argmax_noalloc(int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra,
+                                       const void *hidden /*[M,D]*/, const void *w /*[V+n_extra,D]*/,
+                                       int32_t *argmax /*[M]*/, float *max_logit /*[M]*/,
+                                       float *extra_out /*[M,n_extra]*/, float *logits_dbg /*[M,V]*/,
+                                       uint32_t flags, void *stream);
+
 /* ---- stages 4 + 5: acceptance, smoothing, exit rule (Alg. 1; Sec. 3.3; Appendix) ----
  * Per sequence b:
  *  smoothing  if is_thinking: x = sig on the first observation (n_obs == 0) or when

@@ -27,7 +27,7 @@ EXPORTS = [
     "specexit_draft_tree_level", "specexit_draft_tree_level_workspace_bytes", "specexit_tree_gather",
     "specexit_graph_begin", "specexit_graph_end", "specexit_graph_launch", "specexit_graph_destroy",
     "specexit_workspace_prepare", "specexit_accept_exit", "specexit_kv_compact", "specexit_last_error", "specexit_version", "specexit_profile_events", "specexit_copy_probe",
-    "specexit_workspace_bytes", "specexit_set_dev_status",
+    "specexit_workspace_bytes", "specexit_set_dev_status", "specexit_lmhead_argmax_noalloc",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
 SMOOTH_EWMA, SMOOTH_NONE, SMOOTH_WINDOW, SMOOTH_MOMENTUM, SMOOTH_PARAGRAPH = 0, 1, 2, 3, 4
@@ -116,6 +116,8 @@ def _load() -> C.CDLL:
     lib.specexit_lmhead_argmax_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     lib.specexit_lmhead_argmax.restype = i32
     lib.specexit_lmhead_argmax.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, sz, u32, vp]
+    lib.specexit_lmhead_argmax_noalloc.restype = i32
+    lib.specexit_lmhead_argmax_noalloc.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, u32, vp]
     lib.specexit_accept_exit.restype = i32
     lib.specexit_accept_exit.argtypes = [C.POINTER(ExitCfg), i32, i32, vp, vp, vp, vp, vp, vp, i32,
                                          vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, u32, vp]
@@ -313,6 +315,16 @@ def specexit_lmhead_argmax(dtype: int, M: int, D: int, V: int, n_extra: int, hid
     _check(LIB.specexit_lmhead_argmax(dtype, M, D, V, n_extra, _ptr(hidden), _ptr(w), _ptr(argmax),
                                       _ptr(max_logit), _ptr(extra_out), _ptr(logits_dbg), wp, wb, flags,
                                       _stream(stream)))
+
+
+NOALLOC_SCRATCH_BYTES = 12 << 20
+
+
+def specexit_lmhead_argmax_noalloc(dtype: int, M: int, D: int, V: int, n_extra: int, hidden, w, argmax, max_logit=None,
+                                   extra_out=None, logits_dbg=None, flags: int = 0, stream=None) -> None:
+    _check(LIB.specexit_lmhead_argmax_noalloc(dtype, M, D, V, n_extra, _ptr(hidden), _ptr(w), _ptr(argmax),
+                                              _ptr(max_logit), _ptr(extra_out), _ptr(logits_dbg), flags,
+                                              _stream(stream)))
 
 
 def specexit_accept_exit(cfg: ExitCfg, B: int, n_q: int, block_tok, parent, target_argmax, sig, ctx_len,

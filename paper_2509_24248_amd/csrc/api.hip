@@ -788,6 +788,51 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
                                       n_extra ? extra_out : nullptr, logits_dbg, s), "argmax rows");
 }
 
+namespace {
+// Scratch of specexit_lmhead_argmax_noalloc: one copy per GPU, held until the process ends.
+// In host code the array's name is only a stand-in; its device address comes from
+// hipGetSymbolAddress, once per device, and that address is what the kernels get.
+constexpr size_t kScratchBytes = SPECEXIT_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_addr[kMaxDevices] = {};
+std::mutex g_scratch_mu;
+
+int32_t scratch_of_current_device(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return check_hip(e, "lmhead_argmax_noalloc: hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(SPECEXIT_EUNSUPPORTED, "lmhead_argmax_noalloc: device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_addr[dev]) {
+    void* addr = nullptr;
+    e = hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !addr) return check_hip(e == hipSuccess ? hipErrorInvalidSymbol : e, "lmhead_argmax_noalloc: address of the built-in scratch buffer");
+    g_scratch_addr[dev] = addr;
+  }
+  *out = g_scratch_addr[dev];
+  return SPECEXIT_OK;
+}
+}  // namespace
+
+int32_t specexit_lmhead_argmax_noalloc(int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra,
+                                       const void* hidden, const void* w, int32_t* argmax, float* max_logit,
+                                       float* extra_out, float* logits_dbg, uint32_t flags, void* stream) {
+  HeadPlan h;
+  int32_t rc = make_head_plan(h, dtype, M, D, V, n_extra);
+  if (rc) return rc;
+  const size_t need = specexit_lmhead_argmax_workspace_bytes(dtype, M, D, V, n_extra);
+  if (need > kScratchBytes)
+    return fail(SPECEXIT_EWORKSPACE, "lmhead_argmax_noalloc: this shape needs %zu bytes of scratch, the built-in buffer holds %zu "
+                "(use specexit_lmhead_argmax with a workspace of the caller's)", need, kScratchBytes);
+  void* addr = nullptr;
+  if ((rc = scratch_of_current_device(&addr))) return rc;
+  // every word of the scratch a call reads was written by that same call's GEMM (one candidate per
+  // row and 16-row tile, or the logits of the ALU path): nothing has to start at zero
+  return specexit_lmhead_argmax(dtype, M, D, V, n_extra, hidden, w, argmax, max_logit, extra_out, logits_dbg, addr,
+                                kScratchBytes, flags, stream);
+}
+
 int32_t specexit_accept_exit(const specexit_exit_cfg* cfg, int32_t B, int32_t n_q, const int32_t* block_tok,
                              const int32_t* parent, const int32_t* target_argmax, const float* sig,
                              const int32_t* ctx_len, const int32_t* split_tok, int32_t S, float* ewma,
