@@ -266,14 +266,16 @@ def cpu_baseline(rnd: Round):
         return sec, f"one full round of the same workload and inputs ({sec:.1f} s of numpy float64)"
     # ---- draft forward: the first row of the first step (the cache is read in place: float32 values
     # of the storage type; the row's own entry is written into it)
+    n_sample = min(6, s.B)
     t0 = time.perf_counter()
-    out = O.draft_step(dims, h["w"], dkv.k, dkv.v, h["tok0"][:1], h["g0"][:1], rnd.L[:1],
+    out = O.draft_step(dims, h["w"], dkv.k, dkv.v, h["tok0"][:n_sample], h["g0"][:n_sample], rnd.L[:n_sample],
                        dkv.page_table if dkv.paged else None, dkv.page_size, store=store)
-    t_row = time.perf_counter() - t0
+    t_rows = time.perf_counter() - t0
+    t_row = t_rows / n_sample
     n_rows = s.B * (sum(lv["W"] for lv in rnd.levels) if s.tree else rnd.n_draft_steps)
     # ---- verification attention: a sample of (sequence, query, head) outputs, scaled by visible keys
     r = np.random.default_rng(7)
-    only = [(int(r.integers(s.B)), int(r.integers(s.n_q)), int(r.integers(s.Hq))) for _ in range(32)]
+    only = [(int(r.integers(s.B)), int(r.integers(s.n_q)), int(r.integers(s.Hq))) for _ in range(256)]
     t0 = time.perf_counter()
     O.verify_attn(h["q"], tk.k, tk.v, rnd.L, h["mask"], rnd.scale, tk.page_table if tk.paged else None, tk.page_size, only)
     t_attn_s = time.perf_counter() - t0
@@ -283,12 +285,12 @@ def cpu_baseline(rnd: Round):
     t0 = time.perf_counter()
     am, _, _ = O.lmhead_argmax(h["hid"], h["lm"])
     O.accept_exit(O.ExitCfg(stop_think_token=c.stop_think_token), c.block_tok, h["parent"],
-                  am.reshape(s.B, s.n_q), out["sig"].repeat(s.B, axis=0), rnd.L, c.split_tok, np.zeros((s.B, 3)),
+                  am.reshape(s.B, s.n_q), np.resize(out["sig"], (s.B, 3)), rnd.L, c.split_tok, np.zeros((s.B, 3)),
                   np.zeros(s.B, np.int32), np.ones(s.B, np.int32))
     t_head = time.perf_counter() - t0
     sec = t_row * n_rows + t_attn_s * keys_all / keys_s + t_head
-    what = (f"measured {t_row + t_attn_s + t_head:.1f} s of numpy float64: 1 of the {n_rows} draft-forward rows of the round "
-            f"({t_row:.1f} s, scaled by {n_rows}), 32 of the {s.B * s.n_q * s.Hq} verification-attention outputs "
+    what = (f"measured {t_rows + t_attn_s + t_head:.1f} s of numpy float64: {n_sample} of the {n_rows} draft-forward rows of the round "
+            f"({t_rows:.1f} s, scaled by {n_rows / n_sample:.1f}), {len(only)} of the {s.B * s.n_q * s.Hq} verification-attention outputs "
             f"({t_attn_s:.1f} s, scaled by visible keys x{keys_all / keys_s:.0f}), the whole LM head and accept/exit ({t_head:.1f} s); "
             f"extrapolated round: {sec:.0f} s")
     return sec, what

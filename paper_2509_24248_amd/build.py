@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 # SPECEXIT_LIB names another output file and SPECEXIT_DEFS extra -D flags: side-by-side builds of kernel variants
 LIB = os.environ.get("SPECEXIT_LIB") or os.path.join(HERE, "libspecexit.so")
-SOURCES = ["api.hip", "gemm.hip", "gemv.hip", "attn.hip", "attn_mfma.hip", "draft.hip", "accept_exit.hip", "kv_compact.hip", "tree.hip", "probe.hip"]
+SOURCES = ["api.hip", "gemm.hip", "gemm_wide.hip", "gemv.hip", "attn.hip", "attn_mfma.hip", "draft.hip", "accept_exit.hip", "kv_compact.hip", "tree.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = (["-Rpass-analysis=kernel-resource-usage"] if os.environ.get("SPECEXIT_RESOURCE_REMARKS") else []) + ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-Wall", "-Wextra",
          # packed fp32 VALU forms are kept out of the generated code on purpose

@@ -771,7 +771,7 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
       ProfScope prof(SPECEXIT_PROF_LMHEAD_GEMM, s);
       if ((rc = check_hip(launch_gemm_mfma(g, s), "gemm lm head"))) return rc;
     }
-    return check_hip(launch_argmax_finalize(pv, pi, h.ntiles, M, argmax, max_logit, s), "argmax finalize");
+    return check_hip(launch_argmax_finalize(pv, pi, g.wide ? head_wide_groups(g) : h.ntiles, M, argmax, max_logit, s), "argmax finalize");
   }
   if (bf16) {
     if ((rc = check_hip(launch_unpack_rows(hidden, true, M, D, act, s), "unpack hidden"))) return rc;

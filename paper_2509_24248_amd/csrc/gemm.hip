@@ -179,25 +179,9 @@ __device__ __forceinline__ void stage_activations(const GemmArgs& g, uint4* a_ld
   }
 }
 
-// whether a wave's NT weight tiles share one 4 KB LDS tile (operands then wait in registers)
-__host__ __device__ constexpr bool gemm_wshare(int mt, int nt) { return nt == 1 || mt < 5; }
-
-#ifndef SX_HEAD_AHEAD_MT
-#define SX_HEAD_AHEAD_MT 2
-#endif
-#ifndef SX_HEAD_NT2_MIN_MV
-#define SX_HEAD_NT2_MIN_MV 100000      // activation rows (times planes) from which a head-mode wave takes two tiles
-#endif
-
-// NT weight tiles per wave (head mode only): the wave's tiles tile0 .. tile0 + NT - 1 are 16 NT
-// consecutive rows.  Every activation operand read from LDS then feeds NT matrix instructions and
-// a workgroup covers NT times the rows per staging of the activations and per barrier, which is
-// what bounds the heads over many activation rows (at 144 rows and one tile per wave the LDS
-// would have to deliver its full rate for the weights to stream at HBM speed).
-template <int MT, int PLANES, bool HEAD, int NT>
+template <int MT, int PLANES, bool HEAD>
 __global__ __launch_bounds__(64 * (HEAD ? kHeadWaves : kGemmWaves))
 void k_gemm_mfma(const GemmArgs g) {
-  static_assert(HEAD || NT == 1, "several tiles per wave only in head mode");
   constexpr int NW = HEAD ? kHeadWaves : kGemmWaves;
   // LDS: [activation pieces of one K chunk, or two one-block buffers][per wave: one 16-row x 128-k weight tile, 4 KB]
   // weight tile entry [row][pos] holds the 16-byte piece (pos ^ row) of that row, so both the
@@ -205,13 +189,9 @@ void k_gemm_mfma(const GemmArgs g) {
   extern __shared__ uint4 dyn_lds[];
   const int Mv = g.M * PLANES;
   const int Mvs = gemm_lds_row_stride(Mv);
-  // heads over few rows want LDS (more workgroups per compute unit), heads over many rows registers
-  constexpr bool WSHARE = gemm_wshare(MT, NT);
-  constexpr int kUnrollS = MT * NT >= 10 ? 1 : 4;               // see one_tile
-  constexpr int WT = WSHARE ? 1 : NT;                            // LDS weight tiles per wave
   uint4* a_lds = dyn_lds;
   uint4* w_lds = dyn_lds + (g.kc >> 3) * Mvs;
-  float* rs_lds = reinterpret_cast<float*>(w_lds + NW * WT * 256);   // [M] 1 / rms of the rows (a_mode 3)
+  float* rs_lds = reinterpret_cast<float*>(w_lds + NW * 256);   // [M] 1 / rms of the rows (a_mode 3)
   if (g.a_mode == 3) {
     // one wave per row: lanes take the pieces in turn, then a fixed-order butterfly
     for (int m = threadIdx.x >> 6; m < g.M; m += NW) {
@@ -233,39 +213,31 @@ void k_gemm_mfma(const GemmArgs g) {
   const int lane = threadIdx.x & 63;
   const int wv = threadIdx.x >> 6;
   const int ntiles = (g.N + 15) >> 4;
-  const int tile0 = (blockIdx.x * NW + wv) * NT;
-  // tiles past the last one redo it (same barriers, same requests) and drop the result
+  const int tile = blockIdx.x * NW + wv;
+  const bool active = tile < ntiles;   // waves past the last tile redo it (same barriers, same requests) and drop the result
   const int ks = blockIdx.y;
   const int KB = g.K >> 7;
   const int kb0 = ks * g.kb_per_split;
   const int kb1 = min(KB, kb0 + g.kb_per_split);
+  const int n0 = (active ? tile : ntiles - 1) << 4;
+  const SegRef sg = find_segment(g, n0);
   const size_t row_bytes = static_cast<size_t>(g.K) * 2;
 
   const int pos = lane & 15;
-  bool active[NT];
-  int n0[NT];
-  const char* src[NT][4];
+  const char* src[4];
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
-    active[j] = tile0 + j < ntiles;
-    n0[j] = (active[j] ? tile0 + j : ntiles - 1) << 4;
-    const SegRef sg = find_segment(g, n0[j]);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int r = 4 * i + (lane >> 4);
-      const int lr = min(n0[j] - sg.row0 + r, sg.rows - 1);  // clamp: rows past the end are masked later
-      src[j][i] = sg.base + static_cast<size_t>(lr) * row_bytes + static_cast<size_t>((pos ^ r) << 4);
-    }
+  for (int i = 0; i < 4; ++i) {
+    const int r = 4 * i + (lane >> 4);
+    const int lr = min(n0 - sg.row0 + r, sg.rows - 1);  // clamp: rows past the end are masked later
+    src[i] = sg.base + static_cast<size_t>(lr) * row_bytes + static_cast<size_t>((pos ^ r) << 4);
   }
   const int fr = lane & 15, fq = lane >> 4;
   const int swr = gemm_lds_swizzle(Mv, PLANES, fq);
-  uint4* my = w_lds + wv * WT * 256;
+  uint4* my = w_lds + wv * 256;
 
-  f32x4_t acc[NT][MT];
+  f32x4_t acc[MT];
 #pragma unroll
-  for (int j = 0; j < NT; ++j)
-#pragma unroll
-    for (int t = 0; t < MT; ++t) acc[j][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < MT; ++t) acc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
   // Weight blocks are requested ahead of their use into two register sets used in turn: blocks
   // kb0, kb0 + 2, .. in A, the others in B.  A set is asked for its next block as soon as its
@@ -277,69 +249,42 @@ void k_gemm_mfma(const GemmArgs g) {
   // issued them.  Waves of the last workgroup that have no tile of their own redo the last tile for the
   // same reason and drop the result.
   // Split projections run for a few microseconds only: their first blocks are requested before
-  // the activations are staged.  A head with more than 32 activation rows has at most two
-  // workgroups per compute unit, each held up by barriers per chunk or block: requests that stay in
-  // flight across those keep the memory system busy.  Heads with few rows have the waves to do
-  // that without and load each block where it is used.
-  constexpr bool AHEAD = !HEAD || MT >= SX_HEAD_AHEAD_MT;
+  // the activations are staged.  A head with more than 16 activation rows (times planes) has at most
+  // three workgroups per compute unit, each held up by barriers per chunk or block: requests that stay
+  // in flight across those keep the memory system busy (measured at 16 fp32 rows: 272 -> 263 us).
+  // Heads with fewer rows have the waves to do that without and load each block where it is used.
+  constexpr bool AHEAD = !HEAD || MT >= 2;
   const int kb_last = kb1 - 1;
-  uint4 wA[NT][4], wB[NT][4];
+  uint4 wA[4], wB[4];
   const char* const spare = static_cast<const char*>(g.w[0]);   // where requests past the end are pointed
-  auto request = [&](uint4 (&dst)[NT][4], int kb) {
+  auto request = [&](uint4 (&dst)[4], int kb) {
     const bool real = kb <= kb_last;
     const size_t off = static_cast<size_t>(real ? kb : 0) << 8;
 #pragma unroll
-    for (int j = 0; j < NT; ++j)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) dst[j][i] = load_stream16(real ? src[j][i] + off : spare);
+    for (int i = 0; i < 4; ++i) dst[i] = load_stream16(real ? src[i] + off : spare);
   };
   if constexpr (AHEAD) {
     request(wA, kb0);
     request(wB, kb0 + 1);
   }
-  // one 128-k block: this wave's weight tiles (in wr) pass one after the other through its private
-  // LDS tile, which turns the coalesced rows into MFMA operands (held in registers for the block),
-  // and meet the activation pieces at ab0 (k piece 0, row 0 of the block);
+  // one 128-k block: this wave's weight tile (in wr) through its private LDS tile, transposed
+  // into MFMA operands, against the activation pieces at ab0 (k piece 0, row 0 of the block);
   // dead: the half step past an odd block count
-  auto one_tile = [&](uint4 (&wr)[NT][4], int kb, const uint4* ab0, bool dead) {
+  auto one_tile = [&](uint4 (&wr)[4], int kb, const uint4* ab0, bool dead) {
     if constexpr (!AHEAD) request(wr, kb);
-    // the tiles are private to this wave, whose LDS operations retire in order: compiler fences
-    // are all that separates the writes from the transposed reads (and those from the next writes)
-    auto wave_fence = [] {
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    };
-    uint4 wf[NT][4];
-    if constexpr (WSHARE) {
-      // one LDS tile, the wave's weight tiles pass through it in turn and wait in registers
 #pragma unroll
-      for (int j = 0; j < NT; ++j) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) my[(4 * i + (lane >> 4)) * 16 + pos] = wr[j][i];
-        wave_fence();
-#pragma unroll
-        for (int s = 0; s < 4; ++s) wf[j][s] = my[fr * 16 + ((4 * s + fq) ^ fr)];
-        wave_fence();
-      }
-    } else {
-      // one LDS tile per weight tile, operands read where they are used (fewer registers)
-#pragma unroll
-      for (int j = 0; j < NT; ++j)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) my[j * 256 + (4 * i + (lane >> 4)) * 16 + pos] = wr[j][i];
-      wave_fence();
-    }
+    for (int i = 0; i < 4; ++i) my[(4 * i + (lane >> 4)) * 16 + pos] = wr[i];
     if constexpr (AHEAD) request(wr, kb + 2);
+    // the tile is private to this wave, whose LDS operations retire in order: a compiler
+    // fence is all that separates the writes from the transposed reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const uint4* ab = ab0 + fq * Mvs;
-    // with many accumulators the four k steps stay a loop: unrolled, the scheduler hoists every
-    // operand read of the block to its top and the register allocator spills
-#pragma unroll kUnrollS
-    for (int s = 0; s < 4; ++s) {
-      if constexpr (!WSHARE) {
 #pragma unroll
-        for (int j = 0; j < NT; ++j) wf[j][s] = my[j * 256 + fr * 16 + ((4 * s + fq) ^ fr)];
-      }
+    for (int s = 0; s < 4; ++s) {
+      const uint4 wf = my[fr * 16 + ((4 * s + fq) ^ fr)];
+      const bf16x8_t wa = __builtin_bit_cast(bf16x8_t, wf);
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
         const int v = 16 * t + fr;
@@ -351,20 +296,11 @@ void k_gemm_mfma(const GemmArgs g) {
           if (v >= Mv) af = make_uint4(0, 0, 0, 0);
         }
         if (dead) af = make_uint4(0, 0, 0, 0);
-#ifdef SX_EXP_NO_AREAD
-        af = make_uint4(s + t, fr, fq, kb);
-#endif
-#ifdef SX_EXP_NO_MFMA
-        acc[0][t][0] += __uint_as_float(af.x ^ af.y ^ af.z ^ af.w ^ wf[0][s].x ^ wf[NT - 1][s].w);
-        continue;
-#endif
-#pragma unroll
-        for (int j = 0; j < NT; ++j)
-          acc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wf[j][s]), __builtin_bit_cast(bf16x8_t, af),
-                                                              acc[j][t], 0, 0, 0);
+        acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, __builtin_bit_cast(bf16x8_t, af), acc[t], 0, 0, 0);
       }
     }
-    if constexpr (!WSHARE) wave_fence();   // the next block's writes come after these reads
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
   };
 
   constexpr bool DOUBLE = HEAD && MT >= 5 && PLANES == 1;   // the LM head over more than 64 bf16 rows (a_mode 1)
@@ -398,23 +334,17 @@ void k_gemm_mfma(const GemmArgs g) {
     for (int j = 0; j < NI; ++j)
       if (st_ent[j] >= 0) a_vec[st_ent[j]] = st[j];
     __syncthreads();
-    auto half = [&](uint4 (&wr)[NT][4], int kb, int cur) {
+    auto half = [&](uint4 (&wr)[4], int kb, int cur) {
       const bool dead = kb >= kb1;                     // uniform: every wave skips the same barrier
       const size_t koff = static_cast<size_t>(min(kb + 1, kb_last)) << 7;
-#ifndef SX_EXP_NO_STAGE
 #pragma unroll
       for (int j = 0; j < NI; ++j) st[j] = *reinterpret_cast<const u32x4_t*>(asrc + st_src[j] + koff);
-#endif
       one_tile(wr, kb, a_lds + cur * bufsz, dead);
       if (!dead) {
-#ifndef SX_EXP_NO_STAGE
 #pragma unroll
         for (int j = 0; j < NI; ++j)
           if (st_ent[j] >= 0) a_vec[(cur ^ 1) * bufsz + st_ent[j]] = st[j];
-#endif
-#ifndef SX_EXP_NO_BARRIER
         __syncthreads();
-#endif
       }
     };
     for (int kb = kb0; kb < kb1; kb += 2) {
@@ -423,7 +353,7 @@ void k_gemm_mfma(const GemmArgs g) {
     }
   } else {
     const int kcb = g.kc >> 7;           // 128-element blocks per staged chunk
-    auto half = [&](uint4 (&wr)[NT][4], int kb) {
+    auto half = [&](uint4 (&wr)[4], int kb) {
       const bool dead = kb >= kb1;
       const int in_chunk = (kb - kb0) % kcb;
       if (in_chunk == 0 && !dead) {
@@ -439,26 +369,26 @@ void k_gemm_mfma(const GemmArgs g) {
     }
   }
   // (a head that reports ranked candidates merges them per workgroup below: its idle waves stay)
-  if (!active[0] && (HEAD ? g.top_b <= 1 : g.epi == 0)) return;
+  if (!active && (HEAD ? g.top_b <= 1 : g.epi == 0)) return;
 
   // accumulator layout: lane (c = lane % 16, q = lane / 16) holds rows n0 + 4q + i of
   // activation column 16 t + c
   if (!HEAD) {
-    if (active[0]) {
+    if (active) {
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
         const int v = 16 * t + fr;
         if (v < Mv) {
-          float* dst = g.partial + (static_cast<size_t>(ks) * Mv + v) * g.N + n0[0] + 4 * fq;
+          float* dst = g.partial + (static_cast<size_t>(ks) * Mv + v) * g.N + n0 + 4 * fq;
           if (g.epi != 0) {
             // read by another workgroup of this launch (N is a multiple of 4 here)
-            if (n0[0] + 4 * fq < g.N) store_agent16(dst, acc[0][t][0], acc[0][t][1], acc[0][t][2], acc[0][t][3]);
-          } else if (n0[0] + 4 * fq + 3 < g.N && (g.N & 3) == 0) {
-            *reinterpret_cast<float4*>(dst) = make_float4(acc[0][t][0], acc[0][t][1], acc[0][t][2], acc[0][t][3]);
+            if (n0 + 4 * fq < g.N) store_agent16(dst, acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+          } else if (n0 + 4 * fq + 3 < g.N && (g.N & 3) == 0) {
+            *reinterpret_cast<float4*>(dst) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
           } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-              if (n0[0] + 4 * fq + i < g.N) dst[i] = acc[0][t][i];
+              if (n0 + 4 * fq + i < g.N) dst[i] = acc[t][i];
           }
         }
       }
@@ -485,13 +415,13 @@ void k_gemm_mfma(const GemmArgs g) {
     float4* red = reinterpret_cast<float4*>(dyn_lds);           // the tiles are done with: reuse their LDS
     float* sq_lds = reinterpret_cast<float*>(red + 64 * kGemmWaves);
     float* xs = sq_lds + 64 * kGemmWaves;                       // epi = 2: the group's finished rows [M][128]
-    constexpr int NTH = 64 * kGemmWaves;   // threads of the workgroup
+    constexpr int NT = 64 * kGemmWaves;
     const int items = g.M * 32;                                  // float4 outputs of the group
     int lpi = 1;                                                 // threads sharing one output
-    while (lpi < 16 && items * lpi * 2 <= NTH) lpi <<= 1;
+    while (lpi < 16 && items * lpi * 2 <= NT) lpi <<= 1;
     const int nsl = static_cast<int>(gridDim.y) * PLANES;
     const int n0g = blockIdx.x * (16 * kGemmWaves);
-    for (int base = 0; base < items; base += NTH / lpi) {
+    for (int base = 0; base < items; base += NT / lpi) {
       const int it = base + threadIdx.x / lpi, sub = threadIdx.x % lpi;
       const int m = it >> 5, f = it & 31;
       const int n = n0g + 4 * f;
@@ -547,7 +477,7 @@ void k_gemm_mfma(const GemmArgs g) {
       const RopeArgs& ra = g.rope;
       const int half = ra.d >> 1;
       const int pairs = g.M * 64;                               // (row, pair) items of the group
-      for (int idx = threadIdx.x; idx < pairs; idx += NTH) {
+      for (int idx = threadIdx.x; idx < pairs; idx += NT) {
         const int m = idx >> 6, pr = idx & 63;
         const int hl = pr / half, c = pr - hl * half;           // head inside the group, pair inside the head
         const int hh = n0g / ra.d + hl;                         // head among q heads, then k heads, then v heads
@@ -601,26 +531,22 @@ void k_gemm_mfma(const GemmArgs g) {
   int* ci = reinterpret_cast<int*>(cv + NW * g.M * TB);
   if (merge) __syncthreads();                                 // every wave is done with the activation pieces
 #pragma unroll
-  for (int j = 0; j < NT; ++j) {
-  if (!merge && !active[j]) continue;          // (with ranked candidates NT is 1 and idle waves stay for the merge)
-  const int tile = tile0 + j;
-#pragma unroll
   for (int t = 0; t < MT; ++t) {
     const int v = 16 * t + fr;
     float val[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      val[i] = acc[j][t][i];
-      if (PLANES == 2) val[i] += __shfl_xor(acc[j][t][i], 1, 64);
+      val[i] = acc[t][i];
+      if (PLANES == 2) val[i] += __shfl_xor(acc[t][i], 1, 64);
     }
     const bool owner = (v < Mv) && (PLANES == 1 || (fr & 1) == 0);
     const int m = v / PLANES;
     float cur[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int n = n0[j] + 4 * fq + i;
+      const int n = n0 + 4 * fq + i;
       cur[i] = -INFINITY;
-      if (owner && active[j] && n < g.N) {
+      if (owner && active && n < g.N) {
         if (n < g.V) {
           if (g.logits_dbg) g.logits_dbg[static_cast<size_t>(m) * g.V + n] = val[i];
           cur[i] = val[i];
@@ -634,7 +560,7 @@ void k_gemm_mfma(const GemmArgs g) {
       int bi = INT_MAX;
 #pragma unroll
       for (int i = 0; i < 4; ++i)
-        if (cur[i] > bv) { bv = cur[i]; bi = n0[j] + 4 * fq + i; }
+        if (cur[i] > bv) { bv = cur[i]; bi = n0 + 4 * fq + i; }
 #pragma unroll
       for (int o = 16; o < 64; o <<= 1) {
         const float ov = __shfl_xor(bv, o, 64);
@@ -653,10 +579,9 @@ void k_gemm_mfma(const GemmArgs g) {
       if (r + 1 < TB) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (n0[j] + 4 * fq + i == bi) cur[i] = -INFINITY;   // taken: out of the next pass
+          if (n0 + 4 * fq + i == bi) cur[i] = -INFINITY;   // taken: out of the next pass
       }
     }
-  }
   }
   if (merge) {
     __syncthreads();
@@ -905,12 +830,10 @@ bool gemm_mfma_supported(int M, int planes, int K) {
   return (K % 128 == 0) && mt >= 1 && mt <= 9;
 }
 
-#ifndef SX_GEMM_PER_CU
-#define SX_GEMM_PER_CU 2
-#endif
-#ifndef SX_GEMM_MAX_KSPLIT
-#define SX_GEMM_MAX_KSPLIT 16
-#endif
+// Split projections: workgroups that share a compute unit, and the most K ranges (measured at the
+// 32B-like shapes with 16 rows and the 8B-like ones with 8: three per unit 10 % slower on the
+// step's projections, up to 24 ranges the same, at most 8 ranges 5 % slower).
+constexpr int kGemmPerCu = 2, kGemmMaxKsplit = 16;
 
 void choose_ksplit(GemmArgs& g, bool mfma, int num_cus) {
   const int KB = g.K / 128;
@@ -932,20 +855,20 @@ void choose_ksplit(GemmArgs& g, bool mfma, int num_cus) {
     budget = (Mv > 32 ? 32 : 20) * 1024;
   } else {
     // The projections run for some tens of microseconds, so what counts is that all their
-    // workgroups are resident at once and keep enough loads in flight: SX_GEMM_PER_CU workgroups
+    // workgroups are resident at once and keep enough loads in flight: kGemmPerCu workgroups
     // share a compute unit (the activation chunk is sized so that their LDS fits), and K is
     // split until the 128-row groups times the K ranges fill those places.  (One workgroup of
     // 96 KB per compute unit left the gate/up, q/k/v and down projections of the 32B-like shapes
     // with 280-400 workgroups for 256 places: a second, nearly empty round.)
     const int groups = gemm_groups(g.N);
-    const int places = SX_GEMM_PER_CU * num_cus;
+    const int places = kGemmPerCu * num_cus;
     int want = places / groups;
-    if (want > SX_GEMM_MAX_KSPLIT) want = SX_GEMM_MAX_KSPLIT;
+    if (want > kGemmMaxKsplit) want = kGemmMaxKsplit;
     if (want > KB) want = KB;
     if (want < 1) want = 1;
     g.kb_per_split = (KB + want - 1) / want;
     g.ksplit = (KB + g.kb_per_split - 1) / g.kb_per_split;
-    budget = (160 * 1024 - 1024) / SX_GEMM_PER_CU - kGemmWaves * 4096 - 2048;
+    budget = (160 * 1024 - 1024) / kGemmPerCu - kGemmWaves * 4096 - 2048;
   }
   // activations staged in LDS per chunk: the whole K range if it fits the budget
   int kcb = budget / block_bytes;
@@ -957,8 +880,7 @@ void choose_ksplit(GemmArgs& g, bool mfma, int num_cus) {
   // arithmetic: kc = the 256 k the two buffers hold
   g.a_double = g.V >= 0 && g.planes == 1 && g.M > 64 ? 1 : 0;
   if (g.a_double) g.kc = 256;
-  // head mode: weight tiles per wave (launch_gemm_mfma falls back to one when ranked candidates are asked for)
-  g.nt = g.V >= 0 && Mv >= SX_HEAD_NT2_MIN_MV ? 2 : 1;
+  g.wide = head_wide_supported(g) ? 1 : 0;
 }
 
 __global__ void k_zero_i32(int* p, int n) {
@@ -983,50 +905,46 @@ hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s) {
 size_t gemm_mfma_lds_bytes(const GemmArgs& g) {
   // activation pieces, one weight tile per wave, the rows' 1 / rms; the reducing epilogue
   // overlays 512 float4 + 512 float on the front
-  const int nt = (g.V >= 0 && g.top_b <= 1) ? g.nt : 1;
-  const int wt = gemm_wshare(gemm_mt(g.M, g.planes), nt) ? 1 : nt;
-  const size_t main = (static_cast<size_t>(g.kc >> 3) * gemm_lds_row_stride(g.M * g.planes) + static_cast<size_t>(g.V >= 0 ? kHeadWaves : kGemmWaves) * wt * 256) * 16 +
+  const size_t main = (static_cast<size_t>(g.kc >> 3) * gemm_lds_row_stride(g.M * g.planes) + static_cast<size_t>(g.V >= 0 ? kHeadWaves : kGemmWaves) * 256) * 16 +
                       ((static_cast<size_t>(g.M) * sizeof(float) + 15) & ~static_cast<size_t>(15));
   const size_t overlay = g.epi == 0 ? 0 : static_cast<size_t>(64 * kGemmWaves) * 20 + (g.epi == 2 ? static_cast<size_t>(g.M) * 512 : 0);
   return main > overlay ? main : overlay;
 }
 
-template <int MT, int PLANES, bool HEAD, int NT>
+template <int MT, int PLANES, bool HEAD>
 static hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
   // set once per process; a function-local static is initialised under the language's own lock,
   // so first calls from several host threads are safe
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_mfma<MT, PLANES, HEAD, NT>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm_mfma<MT, PLANES, HEAD>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
   if (attr != hipSuccess) return attr;
   constexpr int NW = HEAD ? kHeadWaves : kGemmWaves;
-  const dim3 grid((gemm_ntiles(g.N) + NW * NT - 1) / (NW * NT), g.ksplit);
-  hipLaunchKernelGGL((k_gemm_mfma<MT, PLANES, HEAD, NT>), grid, dim3(64 * NW), gemm_mfma_lds_bytes(g), s, g);
+  const dim3 grid((gemm_ntiles(g.N) + NW - 1) / NW, g.ksplit);
+  hipLaunchKernelGGL((k_gemm_mfma<MT, PLANES, HEAD>), grid, dim3(64 * NW), gemm_mfma_lds_bytes(g), s, g);
   return hipGetLastError();
 }
 
-template <int PLANES, bool HEAD, int NT>
+template <int PLANES, bool HEAD>
 static hipError_t launch_mfma_planes(const GemmArgs& g, hipStream_t s) {
   switch (gemm_mt(g.M, PLANES)) {
-    case 1: return launch_one<1, PLANES, HEAD, NT>(g, s);
-    case 2: return launch_one<2, PLANES, HEAD, NT>(g, s);
-    case 3: return launch_one<3, PLANES, HEAD, NT>(g, s);
-    case 4: return launch_one<4, PLANES, HEAD, NT>(g, s);
-    case 5: return launch_one<5, PLANES, HEAD, NT>(g, s);
-    case 6: return launch_one<6, PLANES, HEAD, NT>(g, s);
-    case 7: return launch_one<7, PLANES, HEAD, NT>(g, s);
-    case 8: return launch_one<8, PLANES, HEAD, NT>(g, s);
-    case 9: return launch_one<9, PLANES, HEAD, NT>(g, s);
+    case 1: return launch_one<1, PLANES, HEAD>(g, s);
+    case 2: return launch_one<2, PLANES, HEAD>(g, s);
+    case 3: return launch_one<3, PLANES, HEAD>(g, s);
+    case 4: return launch_one<4, PLANES, HEAD>(g, s);
+    case 5: return launch_one<5, PLANES, HEAD>(g, s);
+    case 6: return launch_one<6, PLANES, HEAD>(g, s);
+    case 7: return launch_one<7, PLANES, HEAD>(g, s);
+    case 8: return launch_one<8, PLANES, HEAD>(g, s);
+    case 9: return launch_one<9, PLANES, HEAD>(g, s);
     default: return hipErrorInvalidValue;
   }
 }
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
+  if (g.wide) return launch_head_wide(g, s);
   if (g.a_double && g.a_mode != 1) return hipErrorInvalidValue;   // that kernel reads bf16 rows only
-  if (g.V >= 0) {
-    if (g.nt == 2 && g.top_b <= 1) return g.planes == 2 ? launch_mfma_planes<2, true, 2>(g, s) : launch_mfma_planes<1, true, 2>(g, s);
-    return g.planes == 2 ? launch_mfma_planes<2, true, 1>(g, s) : launch_mfma_planes<1, true, 1>(g, s);
-  }
-  return g.planes == 2 ? launch_mfma_planes<2, false, 1>(g, s) : launch_mfma_planes<1, false, 1>(g, s);
+  if (g.V >= 0) return g.planes == 2 ? launch_mfma_planes<2, true>(g, s) : launch_mfma_planes<1, true>(g, s);
+  return g.planes == 2 ? launch_mfma_planes<2, false>(g, s) : launch_mfma_planes<1, false>(g, s);
 }
 
 hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, int ntiles, int M,

@@ -73,7 +73,8 @@ struct GemmArgs {
   int a_vocab;
   int* status;         // device error word or nullptr (first out-of-range token id seen)
   int kc;              // K elements of activations staged in LDS at a time (multiple of 128)
-  int nt;              // head mode: weight tiles per wave (1 or 2), set by choose_ksplit
+  int wide;            // head mode over more than 64 bf16 rows: the kernel of gemm_wide.hip (weights through an LDS
+                       // ring, activations in registers); one candidate per row and workgroup, head_wide_groups() of them
   int a_double;        // set by choose_ksplit: head, one plane, more than 64 rows (a_mode must be 1): two one-block buffers refilled in turn
   float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
   // epi = 1: the workgroup that finishes a 128-row group last adds up the group's partial
@@ -142,6 +143,9 @@ bool gemm_mfma_supported(int M, int planes, int K);
 void choose_ksplit(GemmArgs& g, bool mfma, int num_cus);
 hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
+bool head_wide_supported(const GemmArgs& g);
+int head_wide_groups(const GemmArgs& g);      // workgroups = candidates per activation row
+hipError_t launch_head_wide(const GemmArgs& g, hipStream_t s);
 // reduce per-tile partial argmaxes: one result per activation row
 // (with `sig` set it also applies the signal activations to extra[M][3]: the draft head's epilogue)
 hipError_t launch_argmax_finalize(const float* part_val, const int* part_idx, int ntiles, int M,
