@@ -285,7 +285,7 @@ size_t combine_lds_bytes(int wgrid) { return (static_cast<size_t>((wgrid + 3) & 
 bool attn_plan(AttnArgs& a, int num_cus) {
   // The host knows only the upper bound l_max of the lengths; the kernels deal the keys that
   // are really there to the workgroups in equal shares.  Here only the number of workgroups is
-  // set: as many as are resident at once (two of the matrix-core kernel fit a compute unit),
+  // set: as many as are resident at once (one or two of the matrix-core kernel per compute unit),
   // fewer when even the longest possible caches would leave them less than two granules (128
   // keys) each, more when a share could otherwise exceed what one segment can hold.
   a.use_mfma = attn_mfma_supported(a) ? 1 : 0;
@@ -294,7 +294,8 @@ bool attn_plan(AttnArgs& a, int num_cus) {
   const int64_t gmax = (a.l_max + kAttnGran - 1) / kAttnGran;      // granules of the longest possible unit
   const int64_t tmax = units * gmax;
   if (tmax >= (1ll << 30)) return false;
-  const int64_t resident = static_cast<int64_t>(num_cus) * (a.use_mfma ? 2 : 1);
+  a.stages = a.use_mfma ? attn_mfma_stages(a) : 0;
+  const int64_t resident = static_cast<int64_t>(num_cus) * (a.use_mfma ? attn_mfma_per_cu(a) : 1);
   int64_t w = tmax / 2 < resident ? tmax / 2 : resident;
   if (w < 1) w = 1;
   if (a.use_mfma) {

@@ -29,6 +29,17 @@ namespace {
 constexpr int kNK = 2;                 // tile rings (key groups) per workgroup
 constexpr int kSlot = 16384;           // bytes of one ring slot: K tile then V tile
 constexpr int kORow = 132;             // floats per row of the merge buffer (128 + pad)
+// From kBigFrom waves per ring (more than 48 query rows per KV head) one workgroup is resident per
+// compute unit (its eight to sixteen waves need more than the 96-128 registers per lane that two
+// workgroups would leave them) and its rings take kBigStages slots; below that, two workgroups of
+// two-slot rings.  Measured at 64 / 72 rows per KV head (8B-like tree block / 32B-like chain block):
+// two resident workgroups with spills 41.6 us against 31.3 us with one; two, three and four slots
+// within 3 % of each other at 72 rows.
+constexpr int kBigFrom = 4, kBigStages = 4;
+// K operand reads / V operand read pairs issued ahead of the matrix instructions that use them: as
+// many as the registers allow (one resident workgroup: all eight K reads, four V pairs)
+constexpr int k_ahead(int nr) { return nr >= kBigFrom ? 8 : 4; }
+constexpr int v_ahead(int nr) { return nr >= kBigFrom ? 4 : 3; }
 constexpr int kMaxChunkPages = 2048;   // page ids of one chunk kept in LDS (8 KB)
 
 typedef short s16x4_t __attribute__((ext_vector_type(4)));
@@ -73,13 +84,18 @@ constexpr int front_bytes(int rp, int stages) {
   return kNK * stages * kSlot > rp * kORow * 4 ? kNK * stages * kSlot : rp * kORow * 4;
 }
 
+// waves per SIMD the register allocation has to leave room for: the resident workgroups' waves on
+// four SIMDs
+constexpr int min_waves_per_simd(int nr) { return ((nr < kBigFrom ? 2 : 1) * kNK * nr + 3) / 4; }
+
 // NR waves per ring, each owning RTW 16-row tiles of the queries (rows 16 (rr RTW + t) ..).
 // RTW = 2 halves the LDS reads per query row (K and V operands are fetched once per wave and
 // used for both row tiles) at the price of fewer, fatter waves; measured slower than RTW = 1
 // at R = 72, so the launcher below uses one row tile per wave throughout.
 template <int NR, int RTW, int S, bool PAGED>
-__global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
+__global__ __launch_bounds__(64 * kNK * NR, min_waves_per_simd(NR)) void k_attn_ring(const AttnArgs a) {
   constexpr int RP = 16 * NR * RTW;             // query rows covered (padded)
+  constexpr int kKAhead = k_ahead(NR), kVAhead = v_ahead(NR);
   // LDS: [ring 0: S slots][ring 1: S slots] (later overlaid by the merge buffer [RP][kORow]),
   // then the (max, sum) table for the merge, the schedule's prefix table, the page ids of the segment
   constexpr int kFront = front_bytes(RP, S);
@@ -237,22 +253,46 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
     const char* k_lds = ring + (it % S) * kSlot;
     const char* v_lds = k_lds + 8192;
 
-    // ---- S^T = K Q^T for the two 16-key halves
+    // ---- S^T = K Q^T for the two 16-key halves.  The K operand reads run kKAhead reads ahead of the
+    // matrix instructions that use them, and the first V operand reads are issued here as well (they do
+    // not depend on the softmax).  The scheduler is kept from sinking the reads back to their uses: left
+    // alone it aims at the fewest registers and leaves one LDS round trip per matrix instruction exposed.
     f32x4_t sacc[2][RTW];
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int t = 0; t < RTW; ++t) sacc[j][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    auto kread = [&](int i) {       // read i: k step i / 2, key half i % 2
+      const int ks = i >> 1, j = i & 1;
+      return reinterpret_cast<const uint4*>(k_lds)[(16 * j + fr) * 16 + ((4 * ks + fq) ^ fr)];
+    };
+    // Transpose load of V: within 16 lanes, lane i = 4 e + c points at key e's four values
+    // d0 + 4c .. d0 + 4c + 3 and lane j receives column d0 + j of keys e = 0..3.  Two loads give the
+    // 8 keys of the operand in the order P^T uses: 4q..4q+3 of the first half, then of the second half.
+    const int ve = fr >> 2, vc = fr & 3;
+    const int key0 = 4 * fq + ve, key1 = 16 + key0;
+    s16x4_t vlo[8], vhi[8];
+    auto vread = [&](int dt) {
+      const int chunk = 2 * dt + (vc >> 1);
+      const char* p0 = v_lds + key0 * 256 + ((chunk ^ swz_v(key0)) << 4) + ((vc & 1) << 3);
+      const char* p1 = v_lds + key1 * 256 + ((chunk ^ swz_v(key1)) << 4) + ((vc & 1) << 3);
+      vlo[dt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(lds_ptr_t)p0);
+      vhi[dt] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(lds_ptr_t)p1);
+    };
+    uint4 kf[8];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks)
+    for (int i = 0; i < kKAhead; ++i) kf[i] = kread(i);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const uint4 kf = reinterpret_cast<const uint4*>(k_lds)[(16 * j + fr) * 16 + ((4 * ks + fq) ^ fr)];
+    for (int i = 0; i < 8; ++i) {
+      if (i + kKAhead < 8) kf[i + kKAhead] = kread(i + kKAhead);
+      if (i >= 8 - kVAhead) vread(i - (8 - kVAhead));      // the last K steps also start the V reads
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < RTW; ++t)
-          sacc[j][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf),
-                                                              __builtin_bit_cast(bf16x8_t, qf[ks][t]), sacc[j][t], 0, 0, 0);
-      }
+      for (int t = 0; t < RTW; ++t)
+        sacc[i & 1][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kf[i]),
+                                                                __builtin_bit_cast(bf16x8_t, qf[i >> 1][t]), sacc[i & 1][t], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
 
     // ---- online softmax; lane (row, q) owns keys t0 + 16 j + 4 q + e of its row
     const bool need_mask = t0 + 32 > min(L, s1);
@@ -278,8 +318,7 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
           }
       }
       float mt = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      mt = fmaxf(mt, __shfl_xor(mt, 16, 64));
-      mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      mt = quad_row_max(mt);
       const float m_new = fmaxf(m_run[t], mt);
       float al = 1.f;
       float pr[8];
@@ -308,26 +347,18 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
         }
     }
 
-    // ---- O^T += V^T P^T.  Transpose load: within 16 lanes, lane i = 4 e + c points at key
-    // e's four values d0 + 4c .. d0 + 4c + 3 and lane j receives column d0 + j of keys
-    // e = 0..3.  Two loads give the 8 keys of the operand in the order P^T uses:
-    // 4q..4q+3 of the first half, then 4q..4q+3 of the second half.
-    {
-      const int e = fr >> 2, c = fr & 3;
-      const int key0 = 4 * fq + e, key1 = 16 + key0;
+    // ---- O^T += V^T P^T, the V operand reads kVAhead matrix instructions ahead
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int dt = 0; dt < 8; ++dt) {
-        const int chunk = 2 * dt + (c >> 1);
-        const char* p0 = v_lds + key0 * 256 + ((chunk ^ swz_v(key0)) << 4) + ((c & 1) << 3);
-        const char* p1 = v_lds + key1 * 256 + ((chunk ^ swz_v(key1)) << 4) + ((c & 1) << 3);
-        const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(lds_ptr_t)p0);
-        const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(lds_ptr_t)p1);
-        const uint2 l2 = __builtin_bit_cast(uint2, lo), h2 = __builtin_bit_cast(uint2, hi);
-        const bf16x8_t va = __builtin_bit_cast(bf16x8_t, make_uint4(l2.x, l2.y, h2.x, h2.y));
+    for (int dt = 0; dt < 8; ++dt) {
+      if (dt + kVAhead < 8) vread(dt + kVAhead);
+      __builtin_amdgcn_sched_barrier(0);
+      const uint2 l2 = __builtin_bit_cast(uint2, vlo[dt]), h2 = __builtin_bit_cast(uint2, vhi[dt]);
+      const bf16x8_t va = __builtin_bit_cast(bf16x8_t, make_uint4(l2.x, l2.y, h2.x, h2.y));
 #pragma unroll
-        for (int t = 0; t < RTW; ++t)
-          oacc[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8_t, pf[t]), oacc[dt][t], 0, 0, 0);
-      }
+      for (int t = 0; t < RTW; ++t)
+        oacc[dt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, __builtin_bit_cast(bf16x8_t, pf[t]), oacc[dt][t], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
   __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
@@ -394,25 +425,23 @@ __global__ __launch_bounds__(64 * kNK * NR) void k_attn_ring(const AttnArgs a) {
   }
 }
 
-constexpr int kStages = 2;
-
-template <int NR, int RTW, bool PAGED>
+template <int NR, int RTW, int S, bool PAGED>
 hipError_t launch_one(const AttnArgs& a, hipStream_t s) {
   static_assert(NR * RTW <= 8, "at most 128 query rows");
   // set once per process; a function-local static is initialised under the language's own lock,
   // so first calls from several host threads are safe
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_ring<NR, RTW, kStages, PAGED>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_attn_ring<NR, RTW, S, PAGED>),
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (attr != hipSuccess) return attr;
-  const size_t smem = static_cast<size_t>(front_bytes(16 * NR * RTW, kStages)) + static_cast<size_t>(kNK) * NR * RTW * 16 * 2 * sizeof(float) +
-                      static_cast<size_t>(sched_words(a.B)) * sizeof(int) + (PAGED ? static_cast<size_t>(kMaxChunkPages + 1) * sizeof(int) : 0);
-  hipLaunchKernelGGL((k_attn_ring<NR, RTW, kStages, PAGED>), dim3(a.wgrid), dim3(64 * kNK * NR), smem, s, a);
+  hipLaunchKernelGGL((k_attn_ring<NR, RTW, S, PAGED>), dim3(a.wgrid), dim3(64 * kNK * NR), attn_mfma_lds_bytes(a), s, a);
   return hipGetLastError();
 }
 
 template <int NR, int RTW>
 hipError_t launch_nr(const AttnArgs& a, hipStream_t s) {
-  return a.paged ? launch_one<NR, RTW, true>(a, s) : launch_one<NR, RTW, false>(a, s);
+  if constexpr (NR >= kBigFrom)
+    return a.paged ? launch_one<NR, RTW, kBigStages, true>(a, s) : launch_one<NR, RTW, kBigStages, false>(a, s);
+  return a.paged ? launch_one<NR, RTW, 2, true>(a, s) : launch_one<NR, RTW, 2, false>(a, s);
 }
 
 }  // namespace
@@ -421,6 +450,16 @@ bool attn_mfma_supported(const AttnArgs& a) {
   const int R = (a.Hq / a.Hkv) * a.n_q;
   const bool pow2 = (a.page_size & (a.page_size - 1)) == 0;
   return a.dtype == 1 && a.d == 128 && R <= 128 && (!a.paged || (pow2 && a.page_size >= 16));
+}
+
+// Workgroups per compute unit and ring depth (see kBigFrom).
+int attn_mfma_per_cu(const AttnArgs& a) { return ((a.Hq / a.Hkv) * a.n_q + 15) / 16 >= kBigFrom ? 1 : 2; }
+int attn_mfma_stages(const AttnArgs& a) { return attn_mfma_per_cu(a) == 1 ? kBigStages : 2; }
+
+size_t attn_mfma_lds_bytes(const AttnArgs& a) {
+  const int rp = 16 * (((a.Hq / a.Hkv) * a.n_q + 15) / 16);
+  return static_cast<size_t>(front_bytes(rp, a.stages)) + static_cast<size_t>(kNK) * rp * 2 * sizeof(float) +
+         static_cast<size_t>(sched_words(a.B)) * sizeof(int) + (a.paged ? static_cast<size_t>(kMaxChunkPages + 1) * sizeof(int) : 0);
 }
 
 int attn_mfma_max_chunk(const AttnArgs& a) { return a.paged ? kMaxChunkPages * a.page_size : (1 << 30); }

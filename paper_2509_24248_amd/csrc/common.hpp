@@ -62,6 +62,17 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Maximum over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (the four k groups of a matrix-core
+// accumulator column) without an LDS round trip: the swap instructions hand every lane both halves
+// of the exchange with its partner row (with both operands equal, the first result holds rows
+// 0, 0, 2, 2 and the second rows 1, 1, 3, 3 of 16 lanes; the 32-lane form likewise).
+__device__ __forceinline__ float quad_row_max(float v) {
+  const auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
 // (value, index) pair ordered by larger value, then lower index
 __device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
   return v > bv || (v == bv && i < bi);

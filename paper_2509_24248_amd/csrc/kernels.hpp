@@ -190,9 +190,13 @@ struct AttnArgs {
                              // sequences' granule counts, then the number of workgroups that took part
   int64_t n_pages;           // paged: pages in the pool (page ids are forced into it)
   int* status;               // device error word or nullptr: first out-of-range length / page id seen
+  int stages;                // matrix-core kernel: slots per tile ring (attn_plan)
   int use_mfma;              // matrix-core kernel (bf16, head_dim 128); its maxima are in log2 units
 };
 bool attn_mfma_supported(const AttnArgs& a);
+size_t attn_mfma_lds_bytes(const AttnArgs& a);  // dynamic LDS of the matrix-core kernel as planned
+int attn_mfma_per_cu(const AttnArgs& a);        // its workgroups per compute unit
+int attn_mfma_stages(const AttnArgs& a);        // and slots per tile ring
 int attn_mfma_max_chunk(const AttnArgs& a);   // longest chunk the matrix-core kernel takes
 int attn_slots(const AttnArgs& a);            // partial-result slots a launch can write
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t s);
