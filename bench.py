@@ -364,7 +364,8 @@ def main():
     n_steps = rnd.n_draft_steps if rnd.levels is None else len(rnd.levels)
     mk = lambda n: [torch.cuda.Event(enable_timing=True) for _ in range(n)]
     prof = {"draft_head_gemm": (sx.PROF_DRAFT_HEAD_GEMM, K * n_steps), "draft_attn_split": (sx.PROF_DRAFT_ATTN, K * n_steps),
-            "lmhead_gemm": (sx.PROF_LMHEAD_GEMM, K), "verify_attn_split": (sx.PROF_VERIFY_ATTN, K)}
+            "lmhead_gemm": (sx.PROF_LMHEAD_GEMM, K), "verify_attn_split": (sx.PROF_VERIFY_ATTN, K),
+            "draft_proj_in": (sx.PROF_DRAFT_PROJ_IN, K * n_steps), "draft_proj_out": (sx.PROF_DRAFT_PROJ_OUT, K * n_steps)}
     evs = {}
     for name, (kid, n) in prof.items():
         e0, e1 = mk(n), mk(n)
@@ -494,6 +495,13 @@ def main():
                                   flops=4.0 * shape.n_q * shape.Hq * shape.d * (keys_ctx + shape.B * shape.n_q), launches=1,
                                   what="split-KV verification attention of one target layer"),
     }
+    # the layer's projections as two spans of consecutive launches (the weights once; rows and split-K partial sums are small)
+    qkv_cols = (shape.Hq + 2 * shape.Hkv) * shape.d
+    spec["draft_proj_in"] = dict(bytes=e * (2 * shape.D * shape.D + shape.D * qkv_cols), flops=2.0 * rows * (2 * shape.D * shape.D + shape.D * qkv_cols),
+                                 launches=n_steps, what="span of launches: fuse projection, q|k|v projection with rotary embedding and cache write")
+    spec["draft_proj_out"] = dict(bytes=e * (shape.Hq * shape.d * shape.D + 3 * shape.D * shape.I),
+                                  flops=2.0 * rows * (shape.Hq * shape.d * shape.D + 3 * shape.D * shape.I), launches=n_steps,
+                                  what="span of launches: o projection, gate|up projection, SiLU gate, down projection")
     kernels = {}
     for name, sp in spec.items():
         ms_k = kernel_ms[name]
@@ -507,7 +515,7 @@ def main():
                          # the most the matrix cores can be used while the weights / cache stream at HBM peak
                          "mfma_ceiling_at_hbm_peak": min(1.0, ai / RIDGE),
                          "traffic_bytes_per_launch": stored_traffic(name, shape.name)}
-    top = max(kernels, key=lambda n: kernels[n]["share_of_round"])
+    top = max((n for n in kernels if not n.startswith("draft_proj")), key=lambda n: kernels[n]["share_of_round"])   # single kernels only
     kt = kernels[top]
     out = {
         "metric": "verify rounds/sec (and draft tokens verified/sec) per MI355X",
@@ -534,6 +542,12 @@ def main():
                      "bytes_per_launch": kt["bytes_per_launch"], "avg_launch_ms": kt["avg_launch_ms"]},
         "kernels": kernels,
         "eager_ms_per_call": calls,
+        # algorithmic bytes of one call of the three streaming exports over the per-call times above
+        "eager_GBs_per_call": {
+            "specexit_draft_step": sum(spec[n]["bytes"] for n in ("draft_proj_in", "draft_attn_split", "draft_proj_out", "draft_head_gemm"))
+                                   / (calls["specexit_draft_step"] * 1e-3) / 1e9,
+            "specexit_verify_attn": spec["verify_attn_split"]["bytes"] / (calls["specexit_verify_attn"] * 1e-3) / 1e9,
+            "specexit_lmhead_argmax": spec["lmhead_gemm"]["bytes"] / (calls["specexit_lmhead_argmax"] * 1e-3) / 1e9},
         "per_call_note": f"back-to-back calls of one export; verify_attn cycles through {n_copies} copies of the KV cache "
                          f"({n_copies * kv_alloc / 1e6:.0f} MB in all)" +
                          (" so that no call is served from the 256 MB last-level cache" if n_copies * kv_alloc >= (512 << 20)

@@ -334,8 +334,9 @@ int32_t specexit_kv_compact(const specexit_kv_view *kv, int32_t n_layers, int64_
 
 /* ---- measurement aid -------------------------------------------------------------------
  * Hands the library n pairs of caller-owned hipEvent_t ([host] arrays of handles).  From then
- * on, each launch of the named kernel records the next unused pair around that one kernel on
- * the call's stream (start before, stop after), until the pairs run out; n = 0 disarms.
+ * on, each launch of the named kernel records the next unused pair around that one kernel (for
+ * the ids called spans: around those consecutive launches of one call) on the call's stream
+ * (start before, stop after), until the pairs run out; n = 0 disarms.
  * Returns the number of pairs consumed so far for that kernel when called with n < 0.
  * Arming and recording are serialised by a lock; do not arm while a stream is being captured
  * into a graph. */
@@ -343,6 +344,9 @@ int32_t specexit_kv_compact(const specexit_kv_view *kv, int32_t n_layers, int64_
 #define SPECEXIT_PROF_LMHEAD_GEMM     1 /* GEMM + argmax inside specexit_lmhead_argmax            */
 #define SPECEXIT_PROF_VERIFY_ATTN     2 /* split-KV kernel inside specexit_verify_attn            */
 #define SPECEXIT_PROF_DRAFT_ATTN      3 /* split-KV kernel inside specexit_draft_step             */
+#define SPECEXIT_PROF_DRAFT_PROJ_IN   4 /* span: fuse + q|k|v projections of specexit_draft_step  */
+#define SPECEXIT_PROF_DRAFT_PROJ_OUT  5 /* span: o, gate|up (+ SiLU gate), down projections       */
+#define SPECEXIT_PROF_COUNT           6
 int32_t specexit_profile_events(int32_t kernel, void *const *start_events, void *const *stop_events,
                                 int32_t n);
 

@@ -14,14 +14,14 @@ What is computed (SpecExit, arXiv 2509.24248):
                     (children = the parent's top-ranked tokens), producing the
                     block that tree attention verifies, Alg. 1.
 * verify_attn     - the target's attention over [last accepted token | draft
-                    candidates] with a tree (ancestor) mask, Alg. 1 "forward
-                    through M_t with tree attention".
+                    candidates] with a tree (ancestor) mask: the target pass
+                    of Alg. 1 that verifies the drafted block.
 * lmhead_argmax   - target logits -> next token per block position (greedy),
-                    Alg. 1 "target model recover token".
+                    Alg. 1, the target's own token at each block position.
 * kv_compact      - what the round leaves behind for the next one: the accepted
                     path's K/V entries moved next to the context and the
-                    hidden state of the last accepted node, Alg. 1 "update
-                    KV-cache and hidden states accordingly".
+                    hidden state of the last accepted node: the cache and
+                    hidden-state update that closes a round of Alg. 1.
 * accept_exit     - accepted tokens / accept length / recover token (Alg. 1),
                     EWMA smoothing (Sec. 3.3 "Signal Smoothing", Appendix
                     "Signal Smoothing" EWMA equation, alpha = 0.1; the sliding
@@ -540,7 +540,7 @@ def accept_exit(cfg: ExitCfg, block_tok, parent, target_argmax, sig, ctx_len, sp
 
 
 # ---------------------------------------------------------------------------
-# after the round: cache compaction  (Alg. 1, "update KV-cache and hidden states")
+# after the round: cache compaction  (Alg. 1, last step of a round)
 # ---------------------------------------------------------------------------
 
 def kv_compact(k, v, ctx_len, accept_path, accept_len, page_table=None, page_size=16,

@@ -30,6 +30,7 @@ EXPORTS = [
     "specexit_workspace_bytes", "specexit_set_dev_status", "specexit_lmhead_argmax_noalloc",
 ]
 PROF_DRAFT_HEAD_GEMM, PROF_LMHEAD_GEMM, PROF_VERIFY_ATTN, PROF_DRAFT_ATTN = 0, 1, 2, 3
+PROF_DRAFT_PROJ_IN, PROF_DRAFT_PROJ_OUT = 4, 5
 SMOOTH_EWMA, SMOOTH_NONE, SMOOTH_WINDOW, SMOOTH_MOMENTUM, SMOOTH_PARAGRAPH = 0, 1, 2, 3, 4
 SMOOTH_WORDS = 48
 FLAG_WORKSPACE_PREPARED = 1

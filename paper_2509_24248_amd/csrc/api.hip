@@ -56,7 +56,7 @@ struct ProfSlot {
   std::vector<hipEvent_t> start, stop;
   size_t used = 0;
 };
-ProfSlot g_prof[4];
+ProfSlot g_prof[SPECEXIT_PROF_COUNT];
 std::mutex g_prof_mu;   // arming and recording may come from different host threads
 
 struct ProfScope {
@@ -196,6 +196,7 @@ int32_t make_draft_plan(DraftPlan& p, const specexit_model_desc* d, const specex
   if (d->hidden < 64 || d->hidden % 64 || d->hidden > 8192) return fail(SPECEXIT_EUNSUPPORTED, "draft_step: hidden %d must be a multiple of 64 up to 8192", d->hidden);
   if (d->intermediate < 64 || d->intermediate % 64) return fail(SPECEXIT_EUNSUPPORTED, "draft_step: intermediate %d must be a multiple of 64", d->intermediate);
   if (d->vocab < 1) return fail(SPECEXIT_EINVAL, "draft_step: vocab < 1");
+  if (d->vocab < top_b) return fail(SPECEXIT_EINVAL, "draft_step: top_b %d exceeds the vocabulary (%d)", top_b, d->vocab);
   if (d->rem_activation < 0 || d->rem_activation > 2) return fail(SPECEXIT_EINVAL, "draft_step: rem_activation %d", d->rem_activation);
   int32_t rc = fill_attn(p.attn, kv, nseq, W, d->n_q_heads, "draft_step");
   if (rc) return rc;
@@ -360,6 +361,7 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
   int* const status = status_for(io.flags);
 
   const int gd = gemm_groups(dm.D);
+  g_prof_hook(SPECEXIT_PROF_DRAFT_PROJ_IN, 0, s);
   if (p.gemv) {
     // Few rows: every projection is a row-streaming GEMV whose epilogue finishes the job
     // (residual, rotary embedding + cache write, SiLU gate); the RMSNorms are applied while
@@ -444,6 +446,7 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
                                             b.q_buf, p.attn.paged, draft_kv->k, draft_kv->v, draft_kv->page_table,
                                             p.attn.page_size, p.attn.max_pages, p.attn.l_max, s, p.attn.n_pages, status), "rope"))) return rc;
   }
+  g_prof_hook(SPECEXIT_PROF_DRAFT_PROJ_IN, 1, s);
   AttnArgs at = p.attn;
   at.q = b.q_buf;
   at.ctx_len = io.pos;
@@ -455,6 +458,7 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
   at.status = status;
   attn_carve(at, b.attn_ws);
   if ((rc = check_hip(launch_attn(at, s, &g_prof_hook, SPECEXIT_PROF_DRAFT_ATTN), "draft attention"))) return rc;
+  g_prof_hook(SPECEXIT_PROF_DRAFT_PROJ_OUT, 0, s);
   if (p.gemv) {
     const int piece = 3 * num_cus();
     auto ssq_of = [&](int which) { return b.ssq + static_cast<size_t>(which) * B * piece; };
@@ -530,6 +534,7 @@ int32_t run_draft(DraftPlan& p, const specexit_draft_weights* w, const specexit_
     if ((rc = check_hip(launch_reduce_norm(dm, B, dm.D, b.partial, p.down.ksplit, p.down.planes, b.a_buf, w->ln_final,
                                            nullptr, io.hidden_out, b.act, s), "norm final"))) return rc;
   }
+  g_prof_hook(SPECEXIT_PROF_DRAFT_PROJ_OUT, 1, s);
   // widened head (Eq. 1): argmax (or the top_b best) over the vocabulary rows, three signal rows on the side
   if (p.gemv && p.top_b == 1 && !io.cand_logit) {
     // few rows, argmax only: the head is a row stream like the other projections
@@ -578,7 +583,7 @@ int32_t specexit_copy_probe(const void* src, void* dst, size_t bytes, int32_t no
 }
 
 int32_t specexit_profile_events(int32_t kernel, void* const* start_events, void* const* stop_events, int32_t n) {
-  if (kernel < 0 || kernel > 3) return fail(SPECEXIT_EINVAL, "profile_events: unknown kernel id %d", kernel);
+  if (kernel < 0 || kernel >= SPECEXIT_PROF_COUNT) return fail(SPECEXIT_EINVAL, "profile_events: unknown kernel id %d", kernel);
   std::lock_guard<std::mutex> lock(g_prof_mu);
   ProfSlot& sl = g_prof[kernel];
   if (n < 0) return static_cast<int32_t>(sl.used);

@@ -1,5 +1,5 @@
-"""Pins for the oracle's cache compaction (CPU only).  Alg. 1 only says that the cache is
-updated "accordingly"; what that has to mean is fixed by what the next round computes:
+"""Pins for the oracle's cache compaction (CPU only).  Alg. 1 names the cache update that
+ends a round without defining it; what it has to mean is fixed by what the next round computes:
 attention over the compacted cache must equal attention over the old cache restricted to
 the accepted path.  Further pins: position-coded caches read back as the accepted
 sequence, chains are left untouched, paged and contiguous layouts agree, nothing outside
