@@ -719,7 +719,7 @@ struct HeadPlan {
   bool mfma;
   GemmArgs g;
   int ntiles;
-  size_t act_bytes, partial_bytes, pv_bytes;
+  size_t act_bytes, partial_bytes, pv_bytes, pack_bytes;
 };
 int32_t make_head_plan(HeadPlan& h, int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra) {
   if (!dtype_ok(dtype)) return fail(SPECEXIT_EINVAL, "lmhead_argmax: unknown dtype %d", dtype);
@@ -732,7 +732,8 @@ int32_t make_head_plan(HeadPlan& h, int32_t dtype, int32_t M, int32_t D, int32_t
   h.ntiles = gemm_ntiles(V + n_extra);
   h.act_bytes = (!h.mfma && dtype == SPECEXIT_BF16) ? sizeof(float) * M * D : 0;
   h.partial_bytes = h.mfma ? 0 : sizeof(float) * M * (static_cast<size_t>(V) + n_extra);
-  h.pv_bytes = h.mfma ? sizeof(float) * M * h.ntiles : 0;
+  h.pv_bytes = h.mfma ? sizeof(float) * M * (h.g.wide ? head_wide_groups(h.g) : h.ntiles) : 0;
+  h.pack_bytes = h.mfma ? head_wide_pack_bytes(h.g) : 0;
   return SPECEXIT_OK;
 }
 }  // namespace
@@ -740,7 +741,7 @@ int32_t make_head_plan(HeadPlan& h, int32_t dtype, int32_t M, int32_t D, int32_t
 size_t specexit_lmhead_argmax_workspace_bytes(int32_t dtype, int32_t M, int32_t D, int32_t V, int32_t n_extra) {
   HeadPlan h;
   if (make_head_plan(h, dtype, M, D, V, n_extra)) return 0;
-  size_t t = align256(h.act_bytes) + align256(h.partial_bytes) + 2 * align256(h.pv_bytes);
+  size_t t = align256(h.act_bytes) + align256(h.partial_bytes) + 2 * align256(h.pv_bytes) + align256(h.pack_bytes);
   return t ? t : 256;
 }
 
@@ -762,7 +763,9 @@ int32_t specexit_lmhead_argmax(int32_t dtype, int32_t M, int32_t D, int32_t V, i
   float* partial = c.take<float>(h.partial_bytes);
   float* pv = c.take<float>(h.pv_bytes);
   int* pi = c.take<int>(h.pv_bytes);
+  char* packed = c.take<char>(h.pack_bytes);
   GemmArgs g = h.g;
+  g.a_packed = packed;
   g.w[0] = w;
   g.extra_out = n_extra ? extra_out : nullptr;
   g.logits_dbg = logits_dbg;
@@ -832,8 +835,8 @@ int32_t specexit_lmhead_argmax_noalloc(int32_t dtype, int32_t M, int32_t D, int3
                 "(use specexit_lmhead_argmax with a workspace of the caller's)", need, kScratchBytes);
   void* addr = nullptr;
   if ((rc = scratch_of_current_device(&addr))) return rc;
-  // every word of the scratch a call reads was written by that same call's GEMM (one candidate per
-  // row and 16-row tile, or the logits of the ALU path): nothing has to start at zero
+  // every word of the scratch a call reads was written by that same call's kernels (argmax candidates,
+  // the activations in operand order, or the logits of the ALU path): nothing has to start at zero
   return specexit_lmhead_argmax(dtype, M, D, V, n_extra, hidden, w, argmax, max_logit, extra_out, logits_dbg, addr,
                                 kScratchBytes, flags, stream);
 }

@@ -880,7 +880,7 @@ void choose_ksplit(GemmArgs& g, bool mfma, int num_cus) {
   // arithmetic: kc = the 256 k the two buffers hold
   g.a_double = g.V >= 0 && g.planes == 1 && g.M > 64 ? 1 : 0;
   if (g.a_double) g.kc = 256;
-  g.wide = head_wide_supported(g) ? 1 : 0;
+  head_wide_plan(g, num_cus);
 }
 
 __global__ void k_zero_i32(int* p, int n) {

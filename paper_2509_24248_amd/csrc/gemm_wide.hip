@@ -5,25 +5,35 @@
 // block in LDS, as the kernel for fewer rows does, fills the LDS with activations, leaves two
 // 4 KB weight blocks per wave in flight and makes every wave read all activations from LDS for
 // each 16-row weight tile.  Here the roles are swapped:
-//   - the WEIGHTS of the workgroup's TG tiles (16 rows each) pass through an LDS ring of S stages,
-//     one 128-k block of all TG tiles per stage.  Two producer waves do nothing but bring stages
-//     in with direct global->LDS loads (16 bytes per lane, streaming), S-1 stages ahead; their
-//     load counters hold nothing else, so three stages stay in flight across the barriers.
+//   - one workgroup per compute unit walks an equal share of the weight tiles (16 rows each),
+//     whatever the vocabulary size: no rounds of workgroups, no refill of the pipeline between them;
+//   - the WEIGHTS pass through an LDS ring of S stages, one 128-k block of TG tiles per stage.  Two
+//     producer waves do nothing but bring stages in with direct global->LDS loads (16 bytes per
+//     lane, streaming), S-1 stages ahead; their load counters hold nothing else, so three stages
+//     stay in flight across the barriers;
 //   - the ACTIVATIONS stay in registers: consumer wave c owns RTW 16-row tiles of the rows and
-//     loads their operand pieces of the next k block (L2 hits) while it works on this one.
-//   - every consumer multiplies every weight tile of the stage with its own rows: one LDS read
-//     (the transposed weight operand) feeds RTW matrix instructions.
-// One workgroup barrier per k block hands a landed stage to the consumers and the stage consumed
-// one block earlier back to the producers.
-// What bounds it (measured by leaving parts out, 144 rows): the weight stream alone runs at
-// 5.8 TB/s; the matrix instructions and the LDS reads cost little once the reads are issued a
-// k step ahead; the rest is the activations, which every workgroup fetches again from L2 for every
-// k block (40 KB per 32 KB of weights: halving them took 438 -> 365 us, a quarter 320 us).  The epilogue reduces each activation row's logits
-// over the workgroup's 16 TG weight rows to one (value, index) candidate.
+//     loads their operand pieces of the next k block (L2 hits) while it works on this one, from a
+//     copy of the activations in operand order (k_pack_act) so that a load covers whole cache lines;
+//   - a pass takes 2 TG tiles through all k blocks, the two halves of a k block one after the other,
+//     so the activation pieces of a k block are fetched once for 256 weight rows; every consumer
+//     multiplies every weight tile of a stage with its own rows: one LDS read (the transposed
+//     weight operand) feeds RTW matrix instructions.
+// One workgroup barrier per stage hands a landed stage to the consumers and the stage read
+// before it back to the producers.  The epilogue of a pass reduces each activation row's logits
+// over a half's 16 TG weight rows to one (value, index) candidate.
+// What bounds it (measured by leaving parts out, 144 rows, V = 151936, D = 5120, event times of a
+// stand-alone loop): the producers alone stream at 7 TB/s (230 us), the consumers alone (no weight
+// stream) take 225 us, together 340 us whether the ring has three, four or five stages; of that the
+// LDS reads and barriers cost 45 us, the matrix instructions 45 us, the activation loads 25 us
+// (80 us before they covered whole cache lines: a wave's load straight from the row-major matrix is
+// 16 rows x 64 bytes, and such half-line requests, not their bytes, were the cost).  One row of
+// workgroups per 128 weight rows, refilled five times per compute unit, took 437 us in the same loop.
 #include "common.hpp"
 #include "kernels.hpp"
 
 #include <limits.h>
+
+#include <algorithm>
 
 namespace sx {
 
@@ -43,110 +53,205 @@ __device__ __forceinline__ void load_to_lds16(const void* src, const void* lds_b
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(l), "v"(src) : "memory");
 }
 
-// The consumer side of k_head_wide for a wave that owns RT row tiles (its rows start at
-// 16 * wv * RTW): KB steps, one barrier each, then the argmax epilogue.
-template <int RT, int RTW, int TG, int S>
-__device__ __forceinline__ void consume(const GemmArgs& g, char* lds, int wv, int lane, int tile0, int ntiles, int KB) {
-  constexpr int kStage = TG * 4096;
-  const int fr = lane & 15, fq = lane >> 4;
-  // activation operand pieces of one 128-k block: row 16 (wv RTW + t) + fr, k = 32 s + 8 fq .. + 7
-  // (a row past the last one reads row 0 instead: its accumulator column is that lane's own and is
-  // never written out, and selecting zeros here would make the wave wait for the loads it has only
-  // just issued)
-  const bf16_t* arow[RT];
-#pragma unroll
-  for (int t = 0; t < RT; ++t) {
-    const int m = 16 * (wv * RTW + t) + fr;
-    arow[t] = static_cast<const bf16_t*>(g.a_src) + static_cast<size_t>(m < g.M ? m : 0) * g.K + 8 * fq;
+// The stages of a workgroup in the order they pass through the ring.  The workgroup's tiles
+// [t_lo, t_hi) are cut into "halves" of TG tiles; a pass takes two halves (the last pass one, if the
+// count is odd) through all k blocks, the halves of a k block one after the other, so that the
+// consumers fetch their activation pieces of a k block once for 2 TG tiles.
+struct StageCursor {
+  int half0, nh, kb, h;   // first half and number of halves of the current pass; k block; half within the pass
+  static constexpr int kNH = 2;
+  __device__ __forceinline__ void start(int nhalf) { half0 = 0; nh = min(kNH, nhalf); kb = 0; h = 0; }
+  __device__ __forceinline__ void advance(int nhalf, int KB) {
+    if (++h < nh) return;
+    h = 0;
+    if (++kb < KB) return;
+    kb = 0;
+    half0 += nh;
+    nh = min(kNH, nhalf - half0);
   }
-  uint4 bA[RT][4], bB[RT][4];
-  auto fetch = [&](uint4 (&dst)[RT][4], int kb) {
-    const size_t off = static_cast<size_t>(min(kb, KB - 1)) << 7;     // past the end: the last block again, unused
+};
+
+// The consumer side of k_head_wide for a wave that owns RT row tiles (its rows start at
+// 16 * wv * RTW): one barrier per stage, an argmax epilogue per pass.
+template <int RT, int RTW, int TG, int S>
+struct Consumer {
+  static constexpr int kStage = TG * 4096;
+  const GemmArgs& g;
+  char* lds;
+  int wv, fr, fq, t_lo, t_hi, KB, slots;
+  const uint4* apack[RT];   // this lane's piece of row tile t in the packed activations, k block 0, k step 0
+  size_t kb_stride;         // uint4 entries from one k block to the next
+  uint4 b[RT][4];   // activation operand pieces of the current k block: row 16 (wv RTW + t) + fr, k = 32 s + 8 fq .. + 7
+  int stage_no;     // stages consumed so far: stage i lives in ring slot i % S
+
+  __device__ __forceinline__ Consumer(const GemmArgs& g_, char* lds_, int wv_, int lane, int t_lo_, int t_hi_, int KB_, int slots_)
+      : g(g_), lds(lds_), wv(wv_), fr(lane & 15), fq(lane >> 4), t_lo(t_lo_), t_hi(t_hi_), KB(KB_), slots(slots_), stage_no(0) {
+    // packed activations: [k block][row tile][k step][lane] 16-byte pieces, so that one load
+    // instruction of a wave reads 1 KB of consecutive bytes
+    const int NT = (static_cast<int>(blockDim.x) / 64 - kProducers) * RTW;
+    kb_stride = static_cast<size_t>(NT) * 256;
+#pragma unroll
+    for (int t = 0; t < RT; ++t) apack[t] = static_cast<const uint4*>(g.a_packed) + static_cast<size_t>(wv * RTW + t) * 256 + lane;
 #pragma unroll
     for (int t = 0; t < RT; ++t)
 #pragma unroll
-      for (int s = 0; s < 4; ++s) dst[t][s] = *reinterpret_cast<const uint4*>(arow[t] + off + 32 * s);
-  };
-  f32x4_t acc[RT][TG];
-#pragma unroll
-  for (int t = 0; t < RT; ++t)
-#pragma unroll
-    for (int j = 0; j < TG; ++j) acc[t][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-  auto step = [&](uint4 (&cur)[RT][4], uint4 (&nxt)[RT][4], int kb) {
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));    // this wave's loads are activation pieces only: block kb is here
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_s_barrier();                // stage kb has landed
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    fetch(nxt, kb + 1);
-    const uint4* stage = reinterpret_cast<const uint4*>(lds + (kb % S) * kStage) + fr * 16;
-    // k steps outermost: between two matrix instructions on the same accumulator lie those of all
-    // other tiles (an accumulator used again right away stalls for the instruction's full latency).
-    // The TG operand reads of the next k step are issued before this k step's matrix instructions,
-    // and the scheduler is kept from sinking them back to their uses (left alone it keeps one read
-    // ahead of each matrix instruction, which exposes the LDS latency TG * 4 times per block).
-    uint4 wf[2][TG];
-#pragma unroll
-    for (int j = 0; j < TG; ++j) wf[0][j] = stage[j * 256 + (fq ^ fr)];
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (s < 3) {
-#pragma unroll
-        for (int j = 0; j < TG; ++j) wf[(s + 1) & 1][j] = stage[j * 256 + ((4 * (s + 1) + fq) ^ fr)];
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int j = 0; j < TG; ++j)
-#pragma unroll
-        for (int t = 0; t < RT; ++t)
-          acc[t][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wf[s & 1][j]), __builtin_bit_cast(bf16x8_t, cur[t][s]),
-                                                              acc[t][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  };
-  // (an odd block count would need a half step: the launcher takes even counts only)
-  fetch(bA, 0);
-  for (int kb = 0; kb < KB; kb += 2) {
-    step(bA, bB, kb);
-    step(bB, bA, kb + 1);
+      for (int s = 0; s < 4; ++s) b[t][s] = apack[t][s * 64];
   }
 
-  // ---- epilogue: lane (c = lane % 16, q = lane / 16) holds weight rows 16 (tile0 + j) + 4 q + i of
-  // activation row 16 (wv RTW + t) + c; rows below V enter the argmax (lowest index on ties), the
-  // rows V.. are the widened head's extra rows
+  // one pass: NH halves starting at half `half0`
+  template <int NH>
+  __device__ __forceinline__ void pass(int half0) {
+    f32x4_t acc[RT][NH * TG];
 #pragma unroll
-  for (int t = 0; t < RT; ++t) {
-    const int m = 16 * (wv * RTW + t) + fr;
-    const bool owner = m < g.M;
-    float bv = -INFINITY;
-    int bi = INT_MAX;
+    for (int t = 0; t < RT; ++t)
 #pragma unroll
-    for (int j = 0; j < TG; ++j) {
+      for (int j = 0; j < NH * TG; ++j) acc[t][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    // The waves go through a stage's four k steps in read groups of CH tiles, the operand reads one
+    // group ahead of the matrix instructions (k steps outermost: between two matrix instructions on the
+    // same accumulator lie those of all other tiles; the scheduler is kept from sinking the reads back
+    // to their uses).  The barrier that hands over the next stage sits before the last group's matrix
+    // instructions, whose operands are in registers by then: the first reads of the next stage are in
+    // flight while those instructions run, so neither the LDS nor the matrix cores idle around a barrier.
+    constexpr int CH = 4;                 // tiles per read group
+    constexpr int NCH = 4 * TG / CH;      // read groups per stage: group c = k step c / (TG / CH), tiles CH (c % (TG / CH)) ..
+    uint4 wf[2][CH];
+    auto wait_stage = [&]() -> const uint4* {
+      __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0): this wave is done reading the stage it leaves
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_s_barrier();                  // the next stage has landed; the one just read is free
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      const uint4* stage = reinterpret_cast<const uint4*>(lds + (stage_no % S) * kStage) + fr * 16;
+      ++stage_no;
+      return stage;
+    };
+    auto read_group = [&](uint4 (&dst)[CH], const uint4* stage, int c) {
+      const int s = c / (TG / CH), j0 = CH * (c % (TG / CH));
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int n = (tile0 + j) * 16 + 4 * fq + i;
-        const float val = acc[t][j][i];
-        if (owner && tile0 + j < ntiles && n < g.N) {
-          if (n < g.V) {
-            if (g.logits_dbg) g.logits_dbg[static_cast<size_t>(m) * g.V + n] = val;
-            if (val > bv) { bv = val; bi = n; }          // n grows with j and i: '>' keeps the lowest index
-          } else if (g.extra_out) {
-            g.extra_out[m * g.n_extra + (n - g.V)] = val;
+      for (int jj = 0; jj < CH; ++jj) dst[jj] = stage[(j0 + jj) * 256 + ((4 * s + fq) ^ fr)];
+    };
+    const uint4* stage = wait_stage();
+    read_group(wf[0], stage, 0);
+#pragma unroll 1
+    for (int kb = 0; kb < KB; ++kb) {
+      // the pieces of the next k block (of the first one again after the last: the next pass starts there)
+      const size_t noff = static_cast<size_t>(kb + 1 == KB ? 0 : kb + 1) * kb_stride;
+#pragma unroll
+      for (int h = 0; h < NH; ++h) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+          const int s = c / (TG / CH), j0 = CH * (c % (TG / CH));
+          if (c + 1 < NCH) {
+            read_group(wf[(c + 1) & 1], stage, c + 1);
+          } else if (h < NH - 1 || kb + 1 < KB) {
+            stage = wait_stage();
+            read_group(wf[0], stage, 0);
           }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int jj = 0; jj < CH; ++jj)
+#pragma unroll
+            for (int t = 0; t < RT; ++t)
+              acc[t][h * TG + j0 + jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wf[c & 1][jj]),
+                                                                                 __builtin_bit_cast(bf16x8_t, b[t][s]), acc[t][h * TG + j0 + jj], 0, 0, 0);
+          // the last half of a k block is done with piece s: fetch the next block's into its place (1 KB
+          // of consecutive bytes per instruction, an L2 hit with a whole stage of lead)
+          if (h == NH - 1 && (c + 1) % (TG / CH) == 0) {
+#pragma unroll
+            for (int t = 0; t < RT; ++t) b[t][s] = apack[t][noff + s * 64];
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
+
+    // ---- epilogue: lane (c = lane % 16, q = lane / 16) holds weight rows 16 (tile0 + j) + 4 q + i of
+    // activation row 16 (wv RTW + t) + c; rows below V enter the argmax (lowest index on ties), the
+    // rows V.. are the widened head's extra rows.  One candidate per row and half.
+    const size_t nslot = static_cast<size_t>(gridDim.x) * slots;
 #pragma unroll
-    for (int o = 16; o < 64; o <<= 1) {
-      const float ov = __shfl_xor(bv, o, 64);
-      const int oi = __shfl_xor(bi, o, 64);
-      if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
-    }
-    if (owner && fq == 0) {
-      g.part_val[static_cast<size_t>(m) * gridDim.x + blockIdx.x] = bv;
-      g.part_idx[static_cast<size_t>(m) * gridDim.x + blockIdx.x] = bi;
+    for (int h = 0; h < NH; ++h) {
+      const int tile0 = t_lo + (half0 + h) * TG;
+#pragma unroll
+      for (int t = 0; t < RT; ++t) {
+        const int m = 16 * (wv * RTW + t) + fr;
+        const bool owner = m < g.M;
+        float bv = -INFINITY;
+        int bi = INT_MAX;
+#pragma unroll
+        for (int j = 0; j < TG; ++j) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int n = (tile0 + j) * 16 + 4 * fq + i;
+            const float val = acc[t][h * TG + j][i];
+            if (owner && tile0 + j < t_hi && n < g.N) {    // (tiles past the workgroup's range hold a copy of its last tile)
+              if (n < g.V) {
+                if (g.logits_dbg) g.logits_dbg[static_cast<size_t>(m) * g.V + n] = val;
+                if (val > bv) { bv = val; bi = n; }          // n grows with j and i: '>' keeps the lowest index
+              } else if (g.extra_out) {
+                g.extra_out[m * g.n_extra + (n - g.V)] = val;
+              }
+            }
+          }
+        }
+#pragma unroll
+        for (int o = 16; o < 64; o <<= 1) {
+          const float ov = __shfl_xor(bv, o, 64);
+          const int oi = __shfl_xor(bi, o, 64);
+          if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
+        }
+        if (owner && fq == 0) {
+          const size_t at = static_cast<size_t>(m) * nslot + static_cast<size_t>(blockIdx.x) * slots + (half0 + h);
+          g.part_val[at] = bv;
+          g.part_idx[at] = bi;
+        }
+      }
     }
   }
+
+  __device__ __forceinline__ void run() {
+    const int nhalf = (t_hi - t_lo + TG - 1) / TG;
+#pragma unroll 1
+    for (int half0 = 0; half0 < nhalf; half0 += 2) {
+      if (half0 + 1 < nhalf) pass<2>(half0);
+      else pass<1>(half0);
+    }
+    // candidate slots this workgroup does not use (its share of the tiles is one half shorter than the longest)
+    if (fq == 0) {
+      const size_t nslot = static_cast<size_t>(gridDim.x) * slots;
+      for (int q = nhalf; q < slots; ++q)
+#pragma unroll
+        for (int t = 0; t < RT; ++t) {
+          const int m = 16 * (wv * RTW + t) + fr;
+          if (m < g.M) {
+            const size_t at = static_cast<size_t>(m) * nslot + static_cast<size_t>(blockIdx.x) * slots + q;
+            g.part_val[at] = -INFINITY;
+            g.part_idx[at] = INT_MAX;
+          }
+        }
+    }
+  }
+};
+
+// Activations [M, K] bf16 -> operand pieces [k block][row tile][k step][lane]: lane (c = lane % 16,
+// q = lane / 16) of piece (kb, tile, s) holds row 16 tile + c, k = 128 kb + 32 s + 8 q .. + 7; rows
+// from M on are zero.  The consumers of k_head_wide then fetch a k block's pieces with loads that
+// cover whole cache lines: read straight from the row-major matrix, the same pieces are 16 rows x
+// 64 bytes per instruction, and those half-line requests, not their bytes, were what the
+// activations cost (144 rows: 80 us of 395 with them, 29 us with full-line loads of the same bytes).
+__global__ __launch_bounds__(256) void k_pack_act(const bf16_t* __restrict__ src, uint4* __restrict__ dst, int M, int K, int NT) {
+  const int lane = threadIdx.x & 63;
+  const int unit = blockIdx.x * 4 + (threadIdx.x >> 6);     // (kb, tile)
+  const int KB = K >> 7;
+  if (unit >= KB * NT) return;
+  const int kb = unit / NT, tile = unit - kb * NT;
+  const int m = 16 * tile + (lane & 15);
+  const bf16_t* row = src + static_cast<size_t>(m < M ? m : 0) * K + 128 * kb + 8 * (lane >> 4);
+  uint4 v[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) v[s] = *reinterpret_cast<const uint4*>(row + 32 * s);
+#pragma unroll
+  for (int s = 0; s < 4; ++s) dst[(static_cast<size_t>(unit) * 4 + s) * 64 + lane] = m < M ? v[s] : uint4{0u, 0u, 0u, 0u};
 }
 
 template <int NC, int RTW, int TG, int S>
@@ -160,54 +265,66 @@ __global__ __launch_bounds__(64 * (NC + kProducers)) void k_head_wide(const Gemm
   const int lane = threadIdx.x & 63;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ntiles = (g.N + 15) >> 4;
-  const int tile0 = blockIdx.x * TG;
+  // this workgroup's share of the weight tiles: equal shares whatever the vocabulary size
+  const int t_lo = static_cast<int>(static_cast<int64_t>(blockIdx.x) * ntiles / gridDim.x);
+  const int t_hi = static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * ntiles / gridDim.x);
+  const int nhalf = (t_hi - t_lo + TG - 1) / TG;
   const int KB = g.K >> 7;
+  const int total = nhalf * KB;                 // stages of this workgroup
   const size_t row_bytes = static_cast<size_t>(g.K) * 2;
 
   if (wv >= NC) {
     // ------------------------------------------------------------------ producer
     // piece j of a stage = rows 4 (j % 4) .. + 3 of tile j / 4; lane l fetches row 4 (j % 4) + l / 16,
     // 16-byte piece (l % 16) ^ row and lands at piece base + 16 l, so that tile entry [row][pos]
-    // holds piece pos ^ row: the consumers' per-row operand reads then touch 16 distinct slots
+    // holds piece pos ^ row: the consumers' per-row operand reads then touch 16 distinct slots.
+    // Every stage is TG tiles: past the workgroup's last tile that tile is fetched again (an L2 hit),
+    // so that every stage counts the same number of loads; the consumers mask those copies.
     const int pw = wv - NC;
-    const char* src[PP];
+    StageCursor cur;
+    cur.start(nhalf);
+    auto issue = [&](int slot) {
+      char* stage = lds + slot * kStage;
+      const int tile0 = t_lo + (cur.half0 + cur.h) * TG;
 #pragma unroll
-    for (int u = 0; u < PP; ++u) {
-      const int j = pw + u * kProducers;
-      const int r = 4 * (j & 3) + (lane >> 4);
-      const int row = min((tile0 + (j >> 2)) * 16 + r, g.N - 1);    // rows past the end repeat the last one, masked later
-      src[u] = static_cast<const char*>(g.w[0]) + static_cast<size_t>(row) * row_bytes + (((lane & 15) ^ r) << 4);
-    }
-    auto issue = [&](int kb) {
-      if (kb >= KB) return;                      // uniform per wave
-      char* stage = lds + (kb % S) * kStage;
-#pragma unroll
-      for (int u = 0; u < PP; ++u) load_to_lds16(src[u] + (static_cast<size_t>(kb) << 8), stage + (pw + u * kProducers) * 1024);
+      for (int u = 0; u < PP; ++u) {
+        const int j = pw + u * kProducers;
+        const int r = 4 * (j & 3) + (lane >> 4);
+        const int tile = min(tile0 + (j >> 2), t_hi - 1);
+        const int row = min(tile * 16 + r, g.N - 1);               // rows past the end repeat the last one, masked later
+        const char* src = static_cast<const char*>(g.w[0]) + static_cast<size_t>(row) * row_bytes + (((lane & 15) ^ r) << 4) +
+                          (static_cast<size_t>(cur.kb) << 8);
+        load_to_lds16(src, stage + j * 1024);
+      }
+      cur.advance(nhalf, KB);
     };
-#pragma unroll
-    for (int kb = 0; kb < S - 1; ++kb) issue(kb);
-    for (int kb = 0; kb < KB; ++kb) {
-      // this wave's pieces of stage kb have landed once at most the pieces of the S-2 stages issued
+    int issued = 0;
+    for (; issued < S - 1 && issued < total; ++issued) issue(issued % S);
+    for (int i = 0; i < total; ++i) {
+      // this wave's pieces of stage i have landed once at most the pieces of the S-2 stages issued
       // after it are outstanding (loads return in order); near the end simply wait for all
-      if (kb + S - 1 < KB) __builtin_amdgcn_s_waitcnt(vmcnt_imm((S - 2) * PP));
+      if (i + S - 1 < total) __builtin_amdgcn_s_waitcnt(vmcnt_imm((S - 2) * PP));
       else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_s_barrier();              // stage kb is complete; the slot of stage kb-1 is free
+      __builtin_amdgcn_s_barrier();              // stage i is complete; the slot of stage i-1 is free
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-      issue(kb + S - 1);
+      if (issued < total) {
+        issue(issued % S);
+        ++issued;
+      }
     }
     return;
   }
 
   // -------------------------------------------------------------------- consumer
   // a wave whose second row tile lies wholly past the last row works on one tile only
-  if (RTW == 2 && 16 * (wv * RTW + 1) >= g.M) consume<1, RTW, TG, S>(g, lds, wv, lane, tile0, ntiles, KB);
-  else consume<RTW, RTW, TG, S>(g, lds, wv, lane, tile0, ntiles, KB);
+  if (RTW == 2 && 16 * (wv * RTW + 1) >= g.M) Consumer<1, RTW, TG, S>(g, lds, wv, lane, t_lo, t_hi, KB, g.wide_slots).run();
+  else Consumer<RTW, RTW, TG, S>(g, lds, wv, lane, t_lo, t_hi, KB, g.wide_slots).run();
 }
 
-// Eight tiles (128 weight rows, 32 KB per stage) and four stages: 96 KB in flight per compute unit.
-// Measured at 144 rows, V = 151936, D = 5120: three stages the same, four tiles per stage (two
-// workgroups per compute unit) 35 % slower, one row tile per consumer wave (nine consumers) the same.
+// Eight tiles (128 weight rows, 32 KB) per stage and four stages: 96 KB in flight per compute unit.
+// Measured at 144 rows, V = 151936, D = 5120: three and five stages the same; three consumer waves of
+// three row tiles with one half per pass no faster (fewer LDS reads, more activation loads).
 constexpr int kWideTiles = 8, kWideStages = 4;
 
 template <int NC, int RTW>
@@ -217,7 +334,10 @@ hipError_t launch_wide(const GemmArgs& g, hipStream_t s) {
   static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_head_wide<NC, RTW, TG, S>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (attr != hipSuccess) return attr;
-  hipLaunchKernelGGL((k_head_wide<NC, RTW, TG, S>), dim3(head_wide_groups(g)), dim3(64 * (NC + kProducers)),
+  const int units = (g.K >> 7) * NC * RTW;
+  hipLaunchKernelGGL(k_pack_act, dim3((units + 3) / 4), dim3(256), 0, s, static_cast<const bf16_t*>(g.a_src),
+                     static_cast<uint4*>(g.a_packed), g.M, g.K, NC * RTW);
+  hipLaunchKernelGGL((k_head_wide<NC, RTW, TG, S>), dim3(g.wide_w), dim3(64 * (NC + kProducers)),
                      static_cast<size_t>(S) * TG * 4096, s, g);
   return hipGetLastError();
 }
@@ -225,13 +345,26 @@ hipError_t launch_wide(const GemmArgs& g, hipStream_t s) {
 }  // namespace
 
 bool head_wide_supported(const GemmArgs& g) {
-  return g.V >= 0 && g.planes == 1 && g.top_b <= 1 && g.M > 64 && g.M <= 160 && g.K % 256 == 0 && g.nseg == 1;
+  return g.V >= 0 && g.planes == 1 && g.top_b <= 1 && g.M > 64 && g.M <= 160 && g.K % 128 == 0 && g.nseg == 1;
 }
 
-int head_wide_groups(const GemmArgs& g) { return (gemm_ntiles(g.N) + kWideTiles - 1) / kWideTiles; }
+// One workgroup per compute unit, each walking an equal share of the weight tiles (at least one
+// stage's worth); candidate slots per workgroup = the halves of the longest share.
+void head_wide_plan(GemmArgs& g, int num_cus) {
+  g.wide = head_wide_supported(g) ? 1 : 0;
+  if (!g.wide) return;
+  const int ntiles = gemm_ntiles(g.N);
+  g.wide_w = std::max(1, std::min(num_cus, ntiles / kWideTiles));
+  g.wide_slots = ((ntiles + g.wide_w - 1) / g.wide_w + kWideTiles - 1) / kWideTiles;
+}
+
+int head_wide_groups(const GemmArgs& g) { return g.wide_w * g.wide_slots; }
+
+// bytes of the packed activations: the row tiles the consumer waves cover (32 rows each) x K
+size_t head_wide_pack_bytes(const GemmArgs& g) { return g.wide ? static_cast<size_t>((g.M + 31) / 32) * 32 * g.K * 2 : 0; }
 
 hipError_t launch_head_wide(const GemmArgs& g, hipStream_t s) {
-  if (!head_wide_supported(g) || g.a_mode != 1) return hipErrorInvalidValue;
+  if (!head_wide_supported(g) || g.a_mode != 1 || g.wide_w < 1 || !g.a_packed) return hipErrorInvalidValue;
   switch ((g.M + 31) / 32) {
     case 3: return launch_wide<3, 2>(g, s);      // 65 ..  96 rows
     case 4: return launch_wide<4, 2>(g, s);      // 97 .. 128

@@ -74,7 +74,10 @@ struct GemmArgs {
   int* status;         // device error word or nullptr (first out-of-range token id seen)
   int kc;              // K elements of activations staged in LDS at a time (multiple of 128)
   int wide;            // head mode over more than 64 bf16 rows: the kernel of gemm_wide.hip (weights through an LDS
-                       // ring, activations in registers); one candidate per row and workgroup, head_wide_groups() of them
+                       // ring, activations in registers); head_wide_groups() candidates per row
+  int wide_w;          //   its workgroups (each walks an equal share of the weight tiles)
+  int wide_slots;      //   candidate slots per workgroup and row
+  void* a_packed;      //   scratch of head_wide_pack_bytes() for the activations in operand order
   int a_double;        // set by choose_ksplit: head, one plane, more than 64 rows (a_mode must be 1): two one-block buffers refilled in turn
   float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
   // epi = 1: the workgroup that finishes a 128-row group last adds up the group's partial
@@ -144,7 +147,9 @@ void choose_ksplit(GemmArgs& g, bool mfma, int num_cus);
 hipError_t launch_gemm_valu(const GemmArgs& g, bool bf16, hipStream_t s);
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s);
 bool head_wide_supported(const GemmArgs& g);
-int head_wide_groups(const GemmArgs& g);      // workgroups = candidates per activation row
+void head_wide_plan(GemmArgs& g, int num_cus);   // sets wide, wide_w, wide_slots
+int head_wide_groups(const GemmArgs& g);      // candidates per activation row
+size_t head_wide_pack_bytes(const GemmArgs& g);
 hipError_t launch_head_wide(const GemmArgs& g, hipStream_t s);
 // reduce per-tile partial argmaxes: one result per activation row
 // (with `sig` set it also applies the signal activations to extra[M][3]: the draft head's epilogue)
