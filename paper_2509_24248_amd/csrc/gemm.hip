@@ -303,70 +303,20 @@ void k_gemm_mfma(const GemmArgs g) {
     __builtin_amdgcn_wave_barrier();
   };
 
-  constexpr bool DOUBLE = HEAD && MT >= 5 && PLANES == 1;   // the LM head over more than 64 bf16 rows (a_mode 1)
-  if constexpr (DOUBLE) {
-    // bf16 activations, two LDS buffers of one 128-k block each.  The next block's pieces are
-    // requested before this block's weights and written to the other buffer after the
-    // arithmetic: one barrier per block, no wait for the staging round trip, and the weight
-    // requests stay in flight across the barrier (loads return in order, so a wave that has
-    // its weights also has the pieces it asked for before them).
-    constexpr int NI = (MT + 1) / 2;                   // 16-byte pieces per thread and block
-    const bf16_t* asrc = static_cast<const bf16_t*>(g.a_src);
-    const int npieces = g.M * 16;
-    const int bufsz = 16 * Mvs;
-    size_t st_src[NI];
-    int st_ent[NI];
-#pragma unroll
-    for (int j = 0; j < NI; ++j) {
-      const int idx = threadIdx.x + j * (64 * NW);
-      const int ii = idx < npieces ? idx : 0;          // past the end: a valid address, nothing written
-      const int sm = ii >> 2;
-      const int s_ = sm / g.M, m = sm - s_ * g.M;
-      const int g8 = s_ * 4 + (ii & 3);
-      st_src[j] = static_cast<size_t>(m) * g.K + g8 * 8;
-      st_ent[j] = idx < npieces ? g8 * Mvs + (m ^ gemm_lds_swizzle(Mv, 1, g8 & 3)) : -1;
+  const int kcb = g.kc >> 7;           // 128-element blocks per staged chunk
+  auto half = [&](uint4 (&wr)[4], int kb) {
+    const bool dead = kb >= kb1;
+    const int in_chunk = (kb - kb0) % kcb;
+    if (in_chunk == 0 && !dead) {
+      if (kb != kb0) __syncthreads();  // everyone is done with the previous chunk
+      stage_activations<PLANES>(g, a_lds, rs_lds, kb << 7, (min(kb1, kb + kcb) - kb) << 7, 64 * NW);
+      __syncthreads();
     }
-    u32x4_t st[NI];
-    u32x4_t* a_vec = reinterpret_cast<u32x4_t*>(a_lds);
-#pragma unroll
-    for (int j = 0; j < NI; ++j) st[j] = *reinterpret_cast<const u32x4_t*>(asrc + st_src[j] + (static_cast<size_t>(min(kb0, kb_last)) << 7));
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-      if (st_ent[j] >= 0) a_vec[st_ent[j]] = st[j];
-    __syncthreads();
-    auto half = [&](uint4 (&wr)[4], int kb, int cur) {
-      const bool dead = kb >= kb1;                     // uniform: every wave skips the same barrier
-      const size_t koff = static_cast<size_t>(min(kb + 1, kb_last)) << 7;
-#pragma unroll
-      for (int j = 0; j < NI; ++j) st[j] = *reinterpret_cast<const u32x4_t*>(asrc + st_src[j] + koff);
-      one_tile(wr, kb, a_lds + cur * bufsz, dead);
-      if (!dead) {
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          if (st_ent[j] >= 0) a_vec[(cur ^ 1) * bufsz + st_ent[j]] = st[j];
-        __syncthreads();
-      }
-    };
-    for (int kb = kb0; kb < kb1; kb += 2) {
-      half(wA, kb, 0);
-      half(wB, kb + 1, 1);
-    }
-  } else {
-    const int kcb = g.kc >> 7;           // 128-element blocks per staged chunk
-    auto half = [&](uint4 (&wr)[4], int kb) {
-      const bool dead = kb >= kb1;
-      const int in_chunk = (kb - kb0) % kcb;
-      if (in_chunk == 0 && !dead) {
-        if (kb != kb0) __syncthreads();  // everyone is done with the previous chunk
-        stage_activations<PLANES>(g, a_lds, rs_lds, kb << 7, (min(kb1, kb + kcb) - kb) << 7, 64 * NW);
-        __syncthreads();
-      }
-      one_tile(wr, kb, a_lds + in_chunk * 16 * Mvs, dead);
-    };
-    for (int kb = kb0; kb < kb1; kb += 2) {
-      half(wA, kb);
-      half(wB, kb + 1);
-    }
+    one_tile(wr, kb, a_lds + in_chunk * 16 * Mvs, dead);
+  };
+  for (int kb = kb0; kb < kb1; kb += 2) {
+    half(wA, kb);
+    half(wB, kb + 1);
   }
   // (a head that reports ranked candidates merges them per workgroup below: its idle waves stay)
   if (!active && (HEAD ? g.top_b <= 1 : g.epi == 0)) return;
@@ -875,11 +825,7 @@ void choose_ksplit(GemmArgs& g, bool mfma, int num_cus) {
   if (kcb < 1) kcb = 1;
   if (kcb > g.kb_per_split) kcb = g.kb_per_split;
   g.kc = kcb * 128;
-  // a head with more than 64 rows of bf16 activations in one plane (the LM head over a large
-  // block) keeps two LDS buffers of one 128-k block each and refills them behind the
-  // arithmetic: kc = the 256 k the two buffers hold
-  g.a_double = g.V >= 0 && g.planes == 1 && g.M > 64 ? 1 : 0;
-  if (g.a_double) g.kc = 256;
+  // the LM head over more than 32 rows has a kernel of its own
   head_wide_plan(g, num_cus);
 }
 
@@ -942,7 +888,6 @@ static hipError_t launch_mfma_planes(const GemmArgs& g, hipStream_t s) {
 
 hipError_t launch_gemm_mfma(const GemmArgs& g, hipStream_t s) {
   if (g.wide) return launch_head_wide(g, s);
-  if (g.a_double && g.a_mode != 1) return hipErrorInvalidValue;   // that kernel reads bf16 rows only
   if (g.V >= 0) return g.planes == 2 ? launch_mfma_planes<2, true>(g, s) : launch_mfma_planes<1, true>(g, s);
   return g.planes == 2 ? launch_mfma_planes<2, false>(g, s) : launch_mfma_planes<1, false>(g, s);
 }

@@ -73,12 +73,11 @@ struct GemmArgs {
   int a_vocab;
   int* status;         // device error word or nullptr (first out-of-range token id seen)
   int kc;              // K elements of activations staged in LDS at a time (multiple of 128)
-  int wide;            // head mode over more than 64 bf16 rows: the kernel of gemm_wide.hip (weights through an LDS
+  int wide;            // head mode over more than 32 bf16 rows: the kernel of gemm_wide.hip (weights through an LDS
                        // ring, activations in registers); head_wide_groups() candidates per row
   int wide_w;          //   its workgroups (each walks an equal share of the weight tiles)
   int wide_slots;      //   candidate slots per workgroup and row
   void* a_packed;      //   scratch of head_wide_pack_bytes() for the activations in operand order
-  int a_double;        // set by choose_ksplit: head, one plane, more than 64 rows (a_mode must be 1): two one-block buffers refilled in turn
   float* partial;      // [ksplit][M*planes][N] fp32, or nullptr in head mode
   // epi = 1: the workgroup that finishes a 128-row group last adds up the group's partial
   // sums in a fixed order (+ residual) and writes the finished rows
