@@ -28,7 +28,9 @@
 // (80 us before they covered whole cache lines: a wave's load straight from the row-major matrix is
 // 16 rows x 64 bytes, and such half-line requests, not their bytes, were the cost).  One row of
 // workgroups per 128 weight rows, refilled five times per compute unit, took 437 us in the same loop.
-// At 56 and 64 rows (V = 151936, D = 4096) it takes 241 us where the LDS-staged kernel took 272 us.
+// At 56 and 64 rows (V = 151936, D = 4096) it takes 241 us where the LDS-staged kernel took 272 us; up to
+// 32 rows (one consumer wave) the LDS-staged kernel is as fast or faster (8 / 16 / 32 rows, D = 5120: 236 /
+// 242 / 271 us against 247 / 249 / 272 us), so this kernel starts at 33 rows.
 #include "common.hpp"
 #include "kernels.hpp"
 

@@ -59,17 +59,20 @@ def test_bf16_alu_fallback_when_k_is_not_a_multiple_of_128():
     run_case(shape, 19, 0, 1, "alu bf16")
 
 
-def test_tie_takes_lowest_index_across_tiles():
-    shape = gen.scaled(gen.config(1), V=4096, D=256)
-    hidden = gen.hidden_rows(shape, 4, 5)
+@pytest.mark.parametrize("M,V,rows", [(4, 4096, (77, 1300, 4000)),        # per-tile candidates of the kernel for few rows
+                                      (40, 4096, (77, 1300, 4000)),       # many-row kernel: three workgroups' shares
+                                      (40, 40000, (5, 140, 30000))])      # ... two halves of one share and a far one
+def test_tie_takes_lowest_index_across_tiles(M, V, rows):
+    shape = gen.scaled(gen.config(1), V=V, D=256)
+    hidden = gen.hidden_rows(shape, M, 5)
     w = gen.lm_head(shape, 5)
     win = gen.store(shape, (hidden[2] / np.abs(hidden[2]).max()).astype(np.float32))
-    for row in (77, 1300, 4000):          # three identical winning rows in different tiles
+    for row in rows:                      # three identical winning rows in different tiles
         w[row] = win
     am_ref, z_ref, _ = O.lmhead_argmax(hidden, w)
-    assert am_ref[2] == 77 and z_ref[2, 77] == z_ref[2, 4000]
+    assert am_ref[2] == rows[0] and z_ref[2, rows[0]] == z_ref[2, rows[2]]
     am, _, _, logits = gpu_lmhead(shape, hidden, w)
-    assert am[2] == 77 and logits[2, 77] == logits[2, 1300] == logits[2, 4000]
+    assert am[2] == rows[0] and logits[2, rows[0]] == logits[2, rows[1]] == logits[2, rows[2]]
 
 
 def test_workspace_and_argument_errors():
