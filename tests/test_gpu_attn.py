@@ -56,6 +56,17 @@ def test_small_tree(paged):
     check(shape, L, kv, q, mask, label="tree")
 
 
+@pytest.mark.parametrize("dtype,B,paged", [("bf16", 1024, False), ("bf16", 333, True), ("f32", 1024, False)])
+def test_many_short_sequences(dtype, B, paged):
+    # the most sequences a launch takes (the length table spans sixteen 64-lane rounds) and an odd
+    # count: every workgroup's share of the keys crosses several (sequence, KV head) units, some empty
+    shape = gen.scaled(gen.config(2), dtype=dtype, B=B, Hq=4, Hkv=2, n_q=2, ctx=(0, 150))
+    L, kv, q, mask = case(shape, 7, paged=paged)
+    L[0] = 0
+    L[B - 1] = 150
+    check(shape, L, kv, q, mask, label="many sequences")
+
+
 def test_paged_equals_contiguous_on_gpu():
     shape = gen.scaled(gen.config(2), B=4, Hq=8, Hkv=2, ctx=(30, 1200))
     L, kv, q, mask = case(shape, 3, paged=False)
