@@ -213,8 +213,12 @@ void k_gemm_mfma(const GemmArgs g) {
   const int lane = threadIdx.x & 63;
   const int wv = threadIdx.x >> 6;
   const int ntiles = (g.N + 15) >> 4;
-  const int tile = blockIdx.x * NW + wv;
-  const bool active = tile < ntiles;   // waves past the last tile redo it (same barriers, same requests) and drop the result
+  // tiles of this workgroup: NW in a row, or (plain projections spread over more workgroups) an equal share
+  const bool spread = !HEAD && g.spread > 0 && g.epi == 0;
+  const int t_lo = spread ? static_cast<int>(static_cast<int64_t>(blockIdx.x) * ntiles / gridDim.x) : static_cast<int>(blockIdx.x) * NW;
+  const int t_hi = spread ? static_cast<int>(static_cast<int64_t>(blockIdx.x + 1) * ntiles / gridDim.x) : ntiles;
+  const int tile = t_lo + wv;
+  const bool active = tile < t_hi;     // waves without a tile go through the same barriers and drop the result
   const int ks = blockIdx.y;
   const int KB = g.K >> 7;
   const int kb0 = ks * g.kb_per_split;
@@ -246,7 +250,7 @@ void k_gemm_mfma(const GemmArgs g) {
   // for one fixed 16-byte piece instead, and an odd block count ends with a half step whose
   // activation operands are forced to zero): a request under a branch makes the compiler merge
   // register sets after it, and the waits of those copies pull the loads back into the step that
-  // issued them.  Waves of the last workgroup that have no tile of their own redo the last tile for the
+  // issued them.  Waves that have no tile of their own (past the last tile) redo the last tile for the
   // same reason and drop the result.
   // Split projections run for a few microseconds only: their first blocks are requested before
   // the activations are staged.  A head with more than 16 activation rows (times planes) has at most
@@ -258,7 +262,7 @@ void k_gemm_mfma(const GemmArgs g) {
   uint4 wA[4], wB[4];
   const char* const spare = static_cast<const char*>(g.w[0]);   // where requests past the end are pointed
   auto request = [&](uint4 (&dst)[4], int kb) {
-    const bool real = kb <= kb_last;
+    const bool real = kb <= kb_last && (active || !spread);   // (a spare wave of a spread launch streams nothing)
     const size_t off = static_cast<size_t>(real ? kb : 0) << 8;
 #pragma unroll
     for (int i = 0; i < 4; ++i) dst[i] = load_stream16(real ? src[i] + off : spare);
@@ -819,6 +823,11 @@ void choose_ksplit(GemmArgs& g, bool mfma, int num_cus) {
     g.kb_per_split = (KB + want - 1) / want;
     g.ksplit = (KB + g.kb_per_split - 1) / g.kb_per_split;
     budget = (160 * 1024 - 1024) / kGemmPerCu - kGemmWaves * 4096 - 2048;
+    // One K range and between half and all of the places taken (the gate/up projection of the 32B-like
+    // shapes: 400 groups for 512 places): compute units with two workgroups then set the time while the
+    // others idle.  The tiles are dealt to all places in equal shares instead (6.25 tiles each there).
+    const int ntiles = gemm_ntiles(g.N);
+    g.spread = (g.ksplit == 1 && groups < places && ntiles >= 4 * places) ? places : 0;
   }
   // activations staged in LDS per chunk: the whole K range if it fits the budget
   int kcb = budget / block_bytes;
@@ -865,7 +874,8 @@ static hipError_t launch_one(const GemmArgs& g, hipStream_t s) {
                                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 256);
   if (attr != hipSuccess) return attr;
   constexpr int NW = HEAD ? kHeadWaves : kGemmWaves;
-  const dim3 grid((gemm_ntiles(g.N) + NW - 1) / NW, g.ksplit);
+  const bool spread = !HEAD && g.spread > 0 && g.epi == 0 && g.ksplit == 1;
+  const dim3 grid(spread ? g.spread : (gemm_ntiles(g.N) + NW - 1) / NW, g.ksplit);
   hipLaunchKernelGGL((k_gemm_mfma<MT, PLANES, HEAD>), grid, dim3(64 * NW), gemm_mfma_lds_bytes(g), s, g);
   return hipGetLastError();
 }

@@ -54,6 +54,8 @@ struct GemmArgs {
   int planes;          // MFMA path: 1 = activations exact in bf16, 2 = bf16 hi + lo parts
   int ksplit;          // number of K ranges
   int kb_per_split;    // MFMA path: 128-element K blocks per range
+  int spread;          // MFMA path, one K range, plain partial output (epi 0): workgroups to spread the 16-row tiles over in
+                       // equal shares (each gets fewer than 8, its spare waves idle), or 0: 8 tiles per workgroup
   const float* act;    // VALU path: fp32 [M][K]
   // MFMA path: where the activations come from
   int a_mode;          // 0: fp32 rows [M][K]; 1: bf16 rows [M][K];
