@@ -541,6 +541,7 @@ def main():
                      "frac": kt["frac_hbm_peak"], "traffic": kt["traffic_bytes_per_launch"],
                      "bytes_per_launch": kt["bytes_per_launch"], "avg_launch_ms": kt["avg_launch_ms"]},
         "kernels": kernels,
+        "other_kernels": {n: v for n, v in kernels.items() if n != top},     # everything but the roofline object's kernel
         "eager_ms_per_call": calls,
         # algorithmic bytes of one call of the three streaming exports over the per-call times above
         "eager_GBs_per_call": {
