@@ -181,18 +181,36 @@ struct Consumer {
         const bool owner = m < g.M;
         float bv = -INFINITY;
         int bi = INT_MAX;
+        // a half that lies wholly inside the share and below the signal rows (all but the last of a
+        // launch) needs no checks per element: the consumers stand still during the epilogue while
+        // the ring fills up, so its length counts
+        const bool plain = !g.logits_dbg && tile0 + TG <= t_hi && (tile0 + TG) * 16 <= g.V;    // uniform
+        if (plain) {
+          const int nb = tile0 * 16 + 4 * fq;
 #pragma unroll
-        for (int j = 0; j < TG; ++j) {
+          for (int j = 0; j < TG; ++j) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int n = (tile0 + j) * 16 + 4 * fq + i;
-            const float val = acc[t][h * TG + j][i];
-            if (owner && tile0 + j < t_hi && n < g.N) {    // (tiles past the workgroup's range hold a copy of its last tile)
-              if (n < g.V) {
-                if (g.logits_dbg) g.logits_dbg[static_cast<size_t>(m) * g.V + n] = val;
-                if (val > bv) { bv = val; bi = n; }          // n grows with j and i: '>' keeps the lowest index
-              } else if (g.extra_out) {
-                g.extra_out[m * g.n_extra + (n - g.V)] = val;
+            for (int i = 0; i < 4; ++i) {
+              const float val = acc[t][h * TG + j][i];
+              const bool up = val > bv;                      // n grows with j and i: '>' keeps the lowest index
+              bv = up ? val : bv;
+              bi = up ? nb + 16 * j + i : bi;
+            }
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < TG; ++j) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const int n = (tile0 + j) * 16 + 4 * fq + i;
+              const float val = acc[t][h * TG + j][i];
+              if (owner && tile0 + j < t_hi && n < g.N) {    // (tiles past the workgroup's range hold a copy of its last tile)
+                if (n < g.V) {
+                  if (g.logits_dbg) g.logits_dbg[static_cast<size_t>(m) * g.V + n] = val;
+                  if (val > bv) { bv = val; bi = n; }
+                } else if (g.extra_out) {
+                  g.extra_out[m * g.n_extra + (n - g.V)] = val;
+                }
               }
             }
           }
