@@ -74,27 +74,28 @@ struct StageCursor {
   }
 };
 
-// The consumer side of k_head_wide for a wave that owns RT row tiles (its rows start at
-// 16 * wv * RTW): one barrier per stage, an argmax epilogue per pass.
-template <int RT, int RTW, int TG, int S>
+// The consumer side of k_head_wide for a wave that owns RT row tiles (from row tile rt0 on) and, of
+// every half, the JN weight tiles from jc0 on (all TG, or half of them when a last odd row tile is
+// shared by two waves): one barrier per stage, an argmax epilogue per pass.  A row has two candidate
+// slots per half, one per column half; a wave that covers the whole half fills the second with nothing.
+template <int RT, int JN, int TG, int S>
 struct Consumer {
   static constexpr int kStage = TG * 4096;
   const GemmArgs& g;
   char* lds;
-  int wv, fr, fq, t_lo, t_hi, KB, slots;
+  int rt0, jc0, fr, fq, t_lo, t_hi, KB, slots;
   const uint4* apack[RT];   // this lane's piece of row tile t in the packed activations, k block 0, k step 0
   size_t kb_stride;         // uint4 entries from one k block to the next
   uint4 b[RT][4];   // activation operand pieces of the current k block: row 16 (wv RTW + t) + fr, k = 32 s + 8 fq .. + 7
   int stage_no;     // stages consumed so far: stage i lives in ring slot i % S
 
-  __device__ __forceinline__ Consumer(const GemmArgs& g_, char* lds_, int wv_, int lane, int t_lo_, int t_hi_, int KB_, int slots_)
-      : g(g_), lds(lds_), wv(wv_), fr(lane & 15), fq(lane >> 4), t_lo(t_lo_), t_hi(t_hi_), KB(KB_), slots(slots_), stage_no(0) {
-    // packed activations: [k block][row tile][k step][lane] 16-byte pieces, so that one load
-    // instruction of a wave reads 1 KB of consecutive bytes
-    const int NT = (static_cast<int>(blockDim.x) / 64 - kProducers) * RTW;
+  __device__ __forceinline__ Consumer(const GemmArgs& g_, char* lds_, int rt0_, int jc0_, int NT, int lane, int t_lo_, int t_hi_, int KB_, int slots_)
+      : g(g_), lds(lds_), rt0(rt0_), jc0(jc0_), fr(lane & 15), fq(lane >> 4), t_lo(t_lo_), t_hi(t_hi_), KB(KB_), slots(slots_), stage_no(0) {
+    // packed activations: [k block][row tile][k step][lane] 16-byte pieces (NT row tiles), so that one
+    // load instruction of a wave reads 1 KB of consecutive bytes
     kb_stride = static_cast<size_t>(NT) * 256;
 #pragma unroll
-    for (int t = 0; t < RT; ++t) apack[t] = static_cast<const uint4*>(g.a_packed) + static_cast<size_t>(wv * RTW + t) * 256 + lane;
+    for (int t = 0; t < RT; ++t) apack[t] = static_cast<const uint4*>(g.a_packed) + static_cast<size_t>(rt0 + t) * 256 + lane;
 #pragma unroll
     for (int t = 0; t < RT; ++t)
 #pragma unroll
@@ -104,11 +105,11 @@ struct Consumer {
   // one pass: NH halves starting at half `half0`
   template <int NH>
   __device__ __forceinline__ void pass(int half0) {
-    f32x4_t acc[RT][NH * TG];
+    f32x4_t acc[RT][NH * JN];
 #pragma unroll
     for (int t = 0; t < RT; ++t)
 #pragma unroll
-      for (int j = 0; j < NH * TG; ++j) acc[t][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      for (int j = 0; j < NH * JN; ++j) acc[t][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     // The waves go through a stage's four k steps in read groups of CH tiles, the operand reads one
     // group ahead of the matrix instructions (k steps outermost: between two matrix instructions on the
@@ -117,7 +118,8 @@ struct Consumer {
     // instructions, whose operands are in registers by then: the first reads of the next stage are in
     // flight while those instructions run, so neither the LDS nor the matrix cores idle around a barrier.
     constexpr int CH = 4;                 // tiles per read group
-    constexpr int NCH = 4 * TG / CH;      // read groups per stage: group c = k step c / (TG / CH), tiles CH (c % (TG / CH)) ..
+    constexpr int GPS = JN / CH;          // read groups per k step
+    constexpr int NCH = 4 * GPS;          // read groups per stage: group c = k step c / GPS, this wave's tiles CH (c % GPS) ..
     uint4 wf[2][CH];
     auto wait_stage = [&]() -> const uint4* {
       __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0): this wave is done reading the stage it leaves
@@ -129,9 +131,9 @@ struct Consumer {
       return stage;
     };
     auto read_group = [&](uint4 (&dst)[CH], const uint4* stage, int c) {
-      const int s = c / (TG / CH), j0 = CH * (c % (TG / CH));
+      const int s = c / GPS, j0 = CH * (c % GPS);
 #pragma unroll
-      for (int jj = 0; jj < CH; ++jj) dst[jj] = stage[(j0 + jj) * 256 + ((4 * s + fq) ^ fr)];
+      for (int jj = 0; jj < CH; ++jj) dst[jj] = stage[(jc0 + j0 + jj) * 256 + ((4 * s + fq) ^ fr)];
     };
     const uint4* stage = wait_stage();
     read_group(wf[0], stage, 0);
@@ -143,7 +145,7 @@ struct Consumer {
       for (int h = 0; h < NH; ++h) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-          const int s = c / (TG / CH), j0 = CH * (c % (TG / CH));
+          const int s = c / GPS, j0 = CH * (c % GPS);
           if (c + 1 < NCH) {
             read_group(wf[(c + 1) & 1], stage, c + 1);
           } else if (h < NH - 1 || kb + 1 < KB) {
@@ -155,11 +157,11 @@ struct Consumer {
           for (int jj = 0; jj < CH; ++jj)
 #pragma unroll
             for (int t = 0; t < RT; ++t)
-              acc[t][h * TG + j0 + jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wf[c & 1][jj]),
-                                                                                 __builtin_bit_cast(bf16x8_t, b[t][s]), acc[t][h * TG + j0 + jj], 0, 0, 0);
+              acc[t][h * JN + j0 + jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wf[c & 1][jj]),
+                                                                                 __builtin_bit_cast(bf16x8_t, b[t][s]), acc[t][h * JN + j0 + jj], 0, 0, 0);
           // the last half of a k block is done with piece s: fetch the next block's into its place (1 KB
           // of consecutive bytes per instruction, an L2 hit with a whole stage of lead)
-          if (h == NH - 1 && (c + 1) % (TG / CH) == 0) {
+          if (h == NH - 1 && (c + 1) % GPS == 0) {
 #pragma unroll
             for (int t = 0; t < RT; ++t) b[t][s] = apack[t][noff + s * 64];
           }
@@ -169,29 +171,29 @@ struct Consumer {
     }
 
     // ---- epilogue: lane (c = lane % 16, q = lane / 16) holds weight rows 16 (tile0 + j) + 4 q + i of
-    // activation row 16 (wv RTW + t) + c; rows below V enter the argmax (lowest index on ties), the
-    // rows V.. are the widened head's extra rows.  One candidate per row and half.
-    const size_t nslot = static_cast<size_t>(gridDim.x) * slots;
+    // activation row 16 (rt0 + t) + c; rows below V enter the argmax (lowest index on ties), the
+    // rows V.. are the widened head's extra rows.  One candidate per row, half and column half.
+    const size_t nslot = static_cast<size_t>(gridDim.x) * slots * 2;
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
-      const int tile0 = t_lo + (half0 + h) * TG;
+      const int tile0 = t_lo + (half0 + h) * TG + jc0;      // this wave's first tile of the half
 #pragma unroll
       for (int t = 0; t < RT; ++t) {
-        const int m = 16 * (wv * RTW + t) + fr;
+        const int m = 16 * (rt0 + t) + fr;
         const bool owner = m < g.M;
         float bv = -INFINITY;
         int bi = INT_MAX;
-        // a half that lies wholly inside the share and below the signal rows (all but the last of a
-        // launch) needs no checks per element: the consumers stand still during the epilogue while
+        // tiles that lie wholly inside the share and below the signal rows (all but the last of a
+        // launch) need no checks per element: the consumers stand still during the epilogue while
         // the ring fills up, so its length counts
-        const bool plain = !g.logits_dbg && tile0 + TG <= t_hi && (tile0 + TG) * 16 <= g.V;    // uniform
+        const bool plain = !g.logits_dbg && tile0 + JN <= t_hi && (tile0 + JN) * 16 <= g.V;    // uniform
         if (plain) {
           const int nb = tile0 * 16 + 4 * fq;
 #pragma unroll
-          for (int j = 0; j < TG; ++j) {
+          for (int j = 0; j < JN; ++j) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-              const float val = acc[t][h * TG + j][i];
+              const float val = acc[t][h * JN + j][i];
               const bool up = val > bv;                      // n grows with j and i: '>' keeps the lowest index
               bv = up ? val : bv;
               bi = up ? nb + 16 * j + i : bi;
@@ -199,11 +201,11 @@ struct Consumer {
           }
         } else {
 #pragma unroll
-          for (int j = 0; j < TG; ++j) {
+          for (int j = 0; j < JN; ++j) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               const int n = (tile0 + j) * 16 + 4 * fq + i;
-              const float val = acc[t][h * TG + j][i];
+              const float val = acc[t][h * JN + j][i];
               if (owner && tile0 + j < t_hi && n < g.N) {    // (tiles past the workgroup's range hold a copy of its last tile)
                 if (n < g.V) {
                   if (g.logits_dbg) g.logits_dbg[static_cast<size_t>(m) * g.V + n] = val;
@@ -222,9 +224,13 @@ struct Consumer {
           if (better(ov, oi, bv, bi)) { bv = ov; bi = oi; }
         }
         if (owner && fq == 0) {
-          const size_t at = static_cast<size_t>(m) * nslot + static_cast<size_t>(blockIdx.x) * slots + (half0 + h);
-          g.part_val[at] = bv;
-          g.part_idx[at] = bi;
+          const size_t at = static_cast<size_t>(m) * nslot + (static_cast<size_t>(blockIdx.x) * slots + (half0 + h)) * 2;
+          g.part_val[at + (jc0 ? 1 : 0)] = bv;
+          g.part_idx[at + (jc0 ? 1 : 0)] = bi;
+          if (JN == TG) {
+            g.part_val[at + 1] = -INFINITY;
+            g.part_idx[at + 1] = INT_MAX;
+          }
         }
       }
     }
@@ -238,16 +244,16 @@ struct Consumer {
       else pass<1>(half0);
     }
     // candidate slots this workgroup does not use (its share of the tiles is one half shorter than the longest)
-    if (fq == 0) {
-      const size_t nslot = static_cast<size_t>(gridDim.x) * slots;
+    if (fq == 0 && jc0 == 0) {
+      const size_t nslot = static_cast<size_t>(gridDim.x) * slots * 2;
       for (int q = nhalf; q < slots; ++q)
 #pragma unroll
         for (int t = 0; t < RT; ++t) {
-          const int m = 16 * (wv * RTW + t) + fr;
+          const int m = 16 * (rt0 + t) + fr;
           if (m < g.M) {
-            const size_t at = static_cast<size_t>(m) * nslot + static_cast<size_t>(blockIdx.x) * slots + q;
-            g.part_val[at] = -INFINITY;
-            g.part_idx[at] = INT_MAX;
+            const size_t at = static_cast<size_t>(m) * nslot + (static_cast<size_t>(blockIdx.x) * slots + q) * 2;
+            g.part_val[at] = g.part_val[at + 1] = -INFINITY;
+            g.part_idx[at] = g.part_idx[at + 1] = INT_MAX;
           }
         }
     }
@@ -275,8 +281,11 @@ __global__ __launch_bounds__(256) void k_pack_act(const bf16_t* __restrict__ src
   for (int s = 0; s < 4; ++s) dst[(static_cast<size_t>(unit) * 4 + s) * 64 + lane] = m < M ? v[s] : uint4{0u, 0u, 0u, 0u};
 }
 
-template <int NC, int RTW, int TG, int S>
-__global__ __launch_bounds__(64 * (NC + kProducers)) void k_head_wide(const GemmArgs g) {
+// NC consumer waves of RTW row tiles, then the producers; SPLIT: the last consumer's second row tile does not
+// exist (an odd number of row tiles), and its one tile is shared with a further wave after the producers,
+// each taking half of the columns: no SIMD then carries three row tiles' worth of matrix instructions.
+template <int NC, int RTW, int TG, int S, bool SPLIT>
+__global__ __launch_bounds__(64 * (NC + kProducers + (SPLIT ? 1 : 0))) void k_head_wide(const GemmArgs g) {
   static_assert((4 * TG) % kProducers == 0, "the pieces of a stage are dealt evenly to the producers");
   constexpr int PP = 4 * TG / kProducers;       // 1 KB pieces (4 weight rows x 256 bytes) per producer and stage
   static_assert((S - 2) * PP < 64, "the load counter has six bits");
@@ -294,7 +303,7 @@ __global__ __launch_bounds__(64 * (NC + kProducers)) void k_head_wide(const Gemm
   const int total = nhalf * KB;                 // stages of this workgroup
   const size_t row_bytes = static_cast<size_t>(g.K) * 2;
 
-  if (wv >= NC) {
+  if (wv >= NC && wv < NC + kProducers) {
     // ------------------------------------------------------------------ producer
     // piece j of a stage = rows 4 (j % 4) .. + 3 of tile j / 4; lane l fetches row 4 (j % 4) + l / 16,
     // 16-byte piece (l % 16) ^ row and lands at piece base + 16 l, so that tile entry [row][pos]
@@ -338,29 +347,42 @@ __global__ __launch_bounds__(64 * (NC + kProducers)) void k_head_wide(const Gemm
   }
 
   // -------------------------------------------------------------------- consumer
-  // a wave whose second row tile lies wholly past the last row works on one tile only
-  if (RTW == 2 && 16 * (wv * RTW + 1) >= g.M) Consumer<1, RTW, TG, S>(g, lds, wv, lane, t_lo, t_hi, KB, g.wide_slots).run();
-  else Consumer<RTW, RTW, TG, S>(g, lds, wv, lane, t_lo, t_hi, KB, g.wide_slots).run();
+  constexpr int NT = NC * RTW;     // row tiles of the packed activations
+  if constexpr (SPLIT) {
+    static_assert(RTW == 2, "a split last tile is the first of a pair");
+    if (wv == NC - 1) Consumer<1, TG / 2, TG, S>(g, lds, (NC - 1) * RTW, 0, NT, lane, t_lo, t_hi, KB, g.wide_slots).run();
+    else if (wv > NC) Consumer<1, TG / 2, TG, S>(g, lds, (NC - 1) * RTW, TG / 2, NT, lane, t_lo, t_hi, KB, g.wide_slots).run();
+    else Consumer<RTW, TG, TG, S>(g, lds, wv * RTW, 0, NT, lane, t_lo, t_hi, KB, g.wide_slots).run();
+  } else {
+    Consumer<RTW, TG, TG, S>(g, lds, wv * RTW, 0, NT, lane, t_lo, t_hi, KB, g.wide_slots).run();
+  }
 }
 
 // Eight tiles (128 weight rows, 32 KB) per stage and four stages: 96 KB in flight per compute unit.
 // Measured at 144 rows, V = 151936, D = 5120: three and five stages the same; three consumer waves of
-// three row tiles with one half per pass no faster (fewer LDS reads, more activation loads).
+// three row tiles with one half per pass no faster (fewer LDS reads, more activation loads); the ninth
+// row tile shared by two waves instead of one wave next to a full consumer on its SIMD: 1.5 % faster.
 constexpr int kWideTiles = 8, kWideStages = 4;
 
-template <int NC, int RTW>
-hipError_t launch_wide(const GemmArgs& g, hipStream_t s) {
+template <int NC, int RTW, bool SPLIT>
+hipError_t launch_wide_as(const GemmArgs& g, hipStream_t s) {
   constexpr int TG = kWideTiles, S = kWideStages;
   // set once per process; a function-local static is initialised under the language's own lock
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_head_wide<NC, RTW, TG, S>),
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&k_head_wide<NC, RTW, TG, S, SPLIT>),
                                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (attr != hipSuccess) return attr;
   const int units = (g.K >> 7) * NC * RTW;
   hipLaunchKernelGGL(k_pack_act, dim3((units + 3) / 4), dim3(256), 0, s, static_cast<const bf16_t*>(g.a_src),
                      static_cast<uint4*>(g.a_packed), g.M, g.K, NC * RTW);
-  hipLaunchKernelGGL((k_head_wide<NC, RTW, TG, S>), dim3(g.wide_w), dim3(64 * (NC + kProducers)),
+  hipLaunchKernelGGL((k_head_wide<NC, RTW, TG, S, SPLIT>), dim3(g.wide_w), dim3(64 * (NC + kProducers + (SPLIT ? 1 : 0))),
                      static_cast<size_t>(S) * TG * 4096, s, g);
   return hipGetLastError();
+}
+
+// an odd number of 16-row tiles: the last one is shared by two waves
+template <int NC, int RTW>
+hipError_t launch_wide(const GemmArgs& g, hipStream_t s) {
+  return ((g.M + 15) / 16) % 2 ? launch_wide_as<NC, RTW, true>(g, s) : launch_wide_as<NC, RTW, false>(g, s);
 }
 
 }  // namespace
@@ -379,7 +401,7 @@ void head_wide_plan(GemmArgs& g, int num_cus) {
   g.wide_slots = ((ntiles + g.wide_w - 1) / g.wide_w + kWideTiles - 1) / kWideTiles;
 }
 
-int head_wide_groups(const GemmArgs& g) { return g.wide_w * g.wide_slots; }
+int head_wide_groups(const GemmArgs& g) { return g.wide_w * g.wide_slots * 2; }
 
 // bytes of the packed activations: the row tiles the consumer waves cover (32 rows each) x K
 size_t head_wide_pack_bytes(const GemmArgs& g) { return g.wide ? static_cast<size_t>((g.M + 31) / 32) * 32 * g.K * 2 : 0; }
