@@ -86,6 +86,7 @@ struct Consumer {
   int rt0, jc0, fr, fq, t_lo, t_hi, KB, slots;
   const uint4* apack[RT];   // this lane's piece of row tile t in the packed activations, k block 0, k step 0
   size_t kb_stride;         // uint4 entries from one k block to the next
+  uint4 bn[RT][2];  // pieces 0 and 1 of the next k block, on their way
   uint4 b[RT][4];   // activation operand pieces of the current k block: row 16 (wv RTW + t) + fr, k = 32 s + 8 fq .. + 7
   int stage_no;     // stages consumed so far: stage i lives in ring slot i % S
 
@@ -159,11 +160,24 @@ struct Consumer {
             for (int t = 0; t < RT; ++t)
               acc[t][h * JN + j0 + jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wf[c & 1][jj]),
                                                                                  __builtin_bit_cast(bf16x8_t, b[t][s]), acc[t][h * JN + j0 + jj], 0, 0, 0);
-          // the last half of a k block is done with piece s: fetch the next block's into its place (1 KB
-          // of consecutive bytes per instruction, an L2 hit with a whole stage of lead)
+          // The next k block's activation pieces (1 KB of consecutive bytes per instruction, L2 hits that
+          // take more than a microsecond under the weight stream).  Pieces 0 and 1, which the next block
+          // needs first, are requested into spare registers at the start of this block and moved over when
+          // the last half is done with the old ones; pieces 2 and 3 are requested into their own place as
+          // soon as the last half is done with them.
+          if (h == 0 && c == 0) {
+#pragma unroll
+            for (int t = 0; t < RT; ++t) {
+              bn[t][0] = apack[t][noff];
+              bn[t][1] = apack[t][noff + 64];
+            }
+          }
           if (h == NH - 1 && (c + 1) % GPS == 0) {
 #pragma unroll
-            for (int t = 0; t < RT; ++t) b[t][s] = apack[t][noff + s * 64];
+            for (int t = 0; t < RT; ++t) {
+              if (s < 2) b[t][s] = bn[t][s];
+              else b[t][s] = apack[t][noff + s * 64];
+            }
           }
           __builtin_amdgcn_sched_barrier(0);
         }
